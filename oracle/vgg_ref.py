@@ -1,0 +1,257 @@
+"""Python face of the fp64 CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+The per-op functions marshal numpy float64 arrays into ``libvgg_ref.so``
+(vgg_ref.c, direct-loop definitions); the two model-level functions compose
+them in the order the paper's VGG19 runs them (section "VGG19 forward pass":
+16 convolutions with bias and ReLU, 5 window maxima, 3 dense layers, softmax;
+section "VGG19 backward pass": the reverse sweep).  Only tests, the smoke
+check and the benchmark's CPU-baseline leg may import this module; it imports
+nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[C.CDLL] = None
+
+# Architecture as given by the workload description (the paper cites the
+# VGG paper for it; the appendix instruction table confirms 16/5/3).
+_CONV_CHANNELS = [(3, 64), (64, 64), (64, 128), (128, 128),
+                  (128, 256), (256, 256), (256, 256), (256, 256),
+                  (256, 512), (512, 512), (512, 512), (512, 512),
+                  (512, 512), (512, 512), (512, 512), (512, 512)]
+_POOL_AFTER = {1, 3, 7, 11, 15}
+
+_dp = C.POINTER(C.c_double)
+_u8p = C.POINTER(C.c_uint8)
+_i32p = C.POINTER(C.c_int32)
+
+
+def lib() -> C.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "libvgg_ref.so")
+        if not os.path.exists(path):
+            from . import build as _b
+            _b.build()
+        _LIB = C.CDLL(path)
+        _LIB.ref_num_threads.restype = C.c_int
+    return _LIB
+
+
+def num_threads() -> int:
+    return int(lib().ref_num_threads())
+
+
+def _d(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.float64 and a.flags.c_contiguous
+    return a.ctypes.data_as(_dp)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _chk(rc: int):
+    if rc != 0:
+        raise ValueError(f"oracle returned {rc}")
+
+
+def conv3x3_fwd(x, w, b=None, relu=True) -> np.ndarray:
+    x, w = _f64(x), _f64(w)
+    b = None if b is None else _f64(b)
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    assert w.shape == (Cout, Cin, 3, 3)
+    y = np.empty((N, Cout, H, W), dtype=np.float64)
+    _chk(lib().ref_conv3x3_fwd(N, Cin, Cout, H, W, _d(x), _d(w), _d(b), int(bool(relu)), _d(y)))
+    return y
+
+
+def conv3x3_bwd_data(g, w) -> np.ndarray:
+    g, w = _f64(g), _f64(w)
+    N, Cout, H, W = g.shape
+    Cin = w.shape[1]
+    assert w.shape == (Cout, Cin, 3, 3)
+    dx = np.empty((N, Cin, H, W), dtype=np.float64)
+    _chk(lib().ref_conv3x3_bwd_data(N, Cin, Cout, H, W, _d(g), _d(w), _d(dx)))
+    return dx
+
+
+def conv3x3_bwd_weight(x, g):
+    x, g = _f64(x), _f64(g)
+    N, Cin, H, W = x.shape
+    Cout = g.shape[1]
+    assert g.shape == (N, Cout, H, W)
+    dw = np.empty((Cout, Cin, 3, 3), dtype=np.float64)
+    db = np.empty((Cout,), dtype=np.float64)
+    _chk(lib().ref_conv3x3_bwd_weight(N, Cin, Cout, H, W, _d(x), _d(g), _d(dw), _d(db)))
+    return dw, db
+
+
+def maxpool2x2(x):
+    x = _f64(x)
+    N, Cc, H, W = x.shape
+    p = np.empty((N, Cc, H // 2, W // 2), dtype=np.float64)
+    arg = np.empty((N, Cc, H // 2, W // 2), dtype=np.uint8)
+    _chk(lib().ref_maxpool2x2(N, Cc, H, W, _d(x), _d(p), arg.ctypes.data_as(_u8p)))
+    return p, arg
+
+
+def maxpool2x2_bwd(dp, arg) -> np.ndarray:
+    dp = _f64(dp)
+    arg = np.ascontiguousarray(arg, dtype=np.uint8)
+    N, Cc, Ho, Wo = dp.shape
+    dx = np.empty((N, Cc, 2 * Ho, 2 * Wo), dtype=np.float64)
+    _chk(lib().ref_maxpool2x2_bwd(N, Cc, 2 * Ho, 2 * Wo, _d(dp), arg.ctypes.data_as(_u8p), _d(dx)))
+    return dx
+
+
+def fc(a, w, b=None, relu=False) -> np.ndarray:
+    a, w = _f64(a), _f64(w)
+    b = None if b is None else _f64(b)
+    N, In = a.shape
+    Out = w.shape[0]
+    assert w.shape == (Out, In)
+    z = np.empty((N, Out), dtype=np.float64)
+    _chk(lib().ref_fc(N, In, Out, _d(a), _d(w), _d(b), int(bool(relu)), _d(z)))
+    return z
+
+
+def fc_bwd(a, w, dz, need_da=True):
+    a, w, dz = _f64(a), _f64(w), _f64(dz)
+    N, In = a.shape
+    Out = w.shape[0]
+    dw = np.empty((Out, In), dtype=np.float64)
+    db = np.empty((Out,), dtype=np.float64)
+    da = np.empty((N, In), dtype=np.float64) if need_da else None
+    _chk(lib().ref_fc_bwd(N, In, Out, _d(a), _d(w), _d(dz), _d(dw), _d(db), _d(da)))
+    return dw, db, da
+
+
+def softmax(z) -> np.ndarray:
+    z = _f64(z)
+    N, K = z.shape
+    p = np.empty_like(z)
+    _chk(lib().ref_softmax(N, K, _d(z), _d(p)))
+    return p
+
+
+def softmax_vjp(p, u) -> np.ndarray:
+    p, u = _f64(p), _f64(u)
+    N, K = p.shape
+    dz = np.empty_like(p)
+    _chk(lib().ref_softmax_vjp(N, K, _d(p), _d(u), _d(dz)))
+    return dz
+
+
+def softmax_xent(p, labels):
+    p = _f64(p)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    N, K = p.shape
+    loss = C.c_double(0.0)
+    dz = np.empty_like(p)
+    _chk(lib().ref_softmax_xent(N, K, _d(p), labels.ctypes.data_as(_i32p), C.byref(loss), _d(dz)))
+    return float(loss.value), dz
+
+
+def relu_bwd(y, dy) -> np.ndarray:
+    y, dy = _f64(y), _f64(dy)
+    g = np.empty_like(y)
+    lib().ref_relu_bwd.argtypes = [C.c_size_t, _dp, _dp, _dp]
+    _chk(lib().ref_relu_bwd(y.size, _d(y), _d(dy), _d(g)))
+    return g
+
+
+def sgd(theta, grad, lr: float) -> np.ndarray:
+    theta = _f64(theta).copy()
+    grad = _f64(grad)
+    lib().ref_sgd.argtypes = [C.c_size_t, _dp, _dp, C.c_double]
+    _chk(lib().ref_sgd(theta.size, _d(theta), _d(grad), float(lr)))
+    return theta
+
+
+# --------------------------------------------------------------------------
+# Whole model
+# --------------------------------------------------------------------------
+
+def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: Sequence,
+                  keep: bool = False) -> Dict[str, object]:
+    """images [N,3,H,W] -> logits, probs (and every intermediate when keep).
+
+    Order of operations: for each of the 16 convolutions, cross-correlate,
+    add bias, clamp at zero; after convolutions 2, 4, 8, 12 and 16 take the
+    2x2 maximum; flatten in C,H,W order; dense+ReLU, dense+ReLU, dense;
+    softmax over the classes of each image.
+    """
+    assert len(conv_w) == 16 and len(fc_w) == 3
+    out: Dict[str, object] = {}
+    acts: List[np.ndarray] = []      # input of every conv layer
+    ys: List[np.ndarray] = []        # post-ReLU output of every conv layer
+    args: Dict[int, np.ndarray] = {}
+    h = _f64(x)
+    for l, (cin, cout) in enumerate(_CONV_CHANNELS):
+        assert conv_w[l].shape == (cout, cin, 3, 3)
+        if keep:
+            acts.append(h)
+        h = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=True)
+        if keep:
+            ys.append(h)
+        if l in _POOL_AFTER:
+            h, a = maxpool2x2(h)
+            if keep:
+                args[l] = a
+    N = h.shape[0]
+    flat = h.reshape(N, -1)
+    z1 = fc(flat, fc_w[0], fc_b[0], relu=True)
+    z2 = fc(z1, fc_w[1], fc_b[1], relu=True)
+    logits = fc(z2, fc_w[2], fc_b[2], relu=False)
+    out["logits"] = logits
+    out["probs"] = softmax(logits)
+    if keep:
+        out.update(conv_in=acts, conv_out=ys, pool_arg=args, pool5=h, flat=flat, z1=z1, z2=z2)
+    return out
+
+
+def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01) -> Dict[str, object]:
+    """One step: forward, mean softmax cross-entropy, full backward, plain SGD.
+
+    Returns loss, logits, probs, the 38 gradient tensors (dconv_w/dconv_b/
+    dfc_w/dfc_b) and the updated parameters (new_*).  ReLU passes gradient
+    where its output is strictly positive; a pool routes its gradient to the
+    recorded first maximum; the first convolution's input gradient is not
+    formed (the paper's optimised backward pass has 47 convolutions, not 48).
+    """
+    f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True)
+    loss, dlogits = softmax_xent(f["probs"], labels)
+    dfc_w = [None] * 3
+    dfc_b = [None] * 3
+    dfc_w[2], dfc_b[2], dz2 = fc_bwd(f["z2"], fc_w[2], dlogits)
+    dz2 = relu_bwd(f["z2"], dz2)
+    dfc_w[1], dfc_b[1], dz1 = fc_bwd(f["z1"], fc_w[1], dz2)
+    dz1 = relu_bwd(f["z1"], dz1)
+    dfc_w[0], dfc_b[0], dflat = fc_bwd(f["flat"], fc_w[0], dz1)
+    d = dflat.reshape(f["pool5"].shape)
+    dconv_w = [None] * 16
+    dconv_b = [None] * 16
+    for l in range(15, -1, -1):
+        if l in _POOL_AFTER:
+            d = maxpool2x2_bwd(d, f["pool_arg"][l])
+        g = relu_bwd(f["conv_out"][l], d)
+        dconv_w[l], dconv_b[l] = conv3x3_bwd_weight(f["conv_in"][l], g)
+        if l > 0:
+            d = conv3x3_bwd_data(g, conv_w[l])
+    res = dict(loss=loss, logits=f["logits"], probs=f["probs"],
+               dconv_w=dconv_w, dconv_b=dconv_b, dfc_w=dfc_w, dfc_b=dfc_b)
+    res["new_conv_w"] = [sgd(conv_w[l], dconv_w[l], lr) for l in range(16)]
+    res["new_conv_b"] = [sgd(conv_b[l], dconv_b[l], lr) for l in range(16)]
+    res["new_fc_w"] = [sgd(fc_w[l], dfc_w[l], lr) for l in range(3)]
+    res["new_fc_b"] = [sgd(fc_b[l], dfc_b[l], lr) for l in range(3)]
+    return res
