@@ -1,0 +1,243 @@
+/*
+ * vgg_mi355x.h -- C ABI of libvgg_mi355x.so: the VGG19 forward pass and
+ * training step as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * The operations are those of the paper's showcase workload (section "VGG19
+ * forward pass", section "VGG19 backward pass", the listing that defines
+ * dense and softmax, and the appendix table of HLO instruction counts):
+ * sixteen 3x3 stride-1 pad-1 convolutions with bias and ReLU, five 2x2
+ * window maxima, three dense layers, softmax; then the reverse sweep.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ *  - Every function returns VGG_OK (0) or a negative vgg_status.  Arguments
+ *    are validated on the host BEFORE anything is enqueued, so an error
+ *    return means no kernel was launched and no buffer was touched.  No
+ *    exceptions, no abort().
+ *  - All tensor pointers are DEVICE pointers unless the name ends in
+ *    `_host`.  The library never allocates or frees device memory and never
+ *    synchronises: every call only enqueues kernels on `stream` (a
+ *    hipStream_t passed as void*; NULL is the default stream).  Buffers are
+ *    owned by the caller and must stay alive until the stream has drained.
+ *  - Tensor pointers must be 16-byte aligned (VGG_ERR_ALIGN otherwise).
+ *  - dtype: VGG_F32 = activations and weights fp32, fp32 MFMA.
+ *           VGG_BF16 = activations and weights bf16 (round-to-nearest-even
+ *           from fp32), fp32 MFMA accumulation, bias and logits fp32.
+ *  - Activation layout at the per-op level is NHWC ([N][H][W][C], C
+ *    fastest).  The model-level calls take the canonical NCHW fp32 image
+ *    batch and canonical parameters (convolution weights [Cout][Cin][3][3],
+ *    dense weights [Out][In], the first dense layer's columns in C,H,W
+ *    flatten order) and convert once.
+ *  - Packed convolution weights: element (tap t = 3*kh+kw, co, ci) lives at
+ *    index (t*Cout + co)*CinP + ci with CinP = vgg_padded_channels(dtype, Cin) and
+ *    zeros in ci >= Cin.
+ *  - `ws`/`ws_bytes`: caller-owned scratch; the matching *_workspace_bytes
+ *    query gives the size required (VGG_ERR_WORKSPACE if smaller).
+ */
+#ifndef VGG_MI355X_H
+#define VGG_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vgg_status {
+    VGG_OK = 0,
+    VGG_ERR_NULL = -1,        /* a required pointer is NULL */
+    VGG_ERR_SHAPE = -2,       /* non-positive size, odd H/W into a pool, label out of range ... */
+    VGG_ERR_DTYPE = -3,       /* dtype is neither VGG_F32 nor VGG_BF16 */
+    VGG_ERR_ALIGN = -4,       /* a tensor pointer is not 16-byte aligned */
+    VGG_ERR_WORKSPACE = -5,   /* ws is NULL or ws_bytes too small */
+    VGG_ERR_LAUNCH = -6,      /* HIP reported an error when a kernel was enqueued */
+    VGG_ERR_UNSUPPORTED = -7  /* valid request the library does not implement (e.g. bf16 training) */
+} vgg_status;
+
+typedef enum vgg_dtype { VGG_F32 = 0, VGG_BF16 = 1 } vgg_dtype;
+
+#define VGG19_NUM_CONV 16
+#define VGG19_NUM_FC 3
+
+/* Whole-network configuration.  The convolution stack is the fixed VGG19
+ * pattern 3-64-64 | 128-128 | 256x4 | 512x4 | 512x4 with a 2x2 max-pool
+ * after each group; the classifier is flat -> fc_hidden -> fc_hidden ->
+ * classes with flat = 512*(H/32)*(W/32).  H and W must be multiples of 32. */
+typedef struct vgg_config {
+    int dtype;      /* vgg_dtype */
+    int N;          /* batch */
+    int H, W;       /* input image size */
+    int fc_hidden;  /* 4096 for the full model, 512 for the tiny one */
+    int classes;    /* 1000 / 10 */
+    float lr;       /* SGD step size used by vgg19_train_step */
+    int flags;      /* reserved, must be 0 */
+} vgg_config;
+
+/* Canonical fp32 parameter (or gradient) set: device pointers. */
+typedef struct vgg19_params {
+    float *conv_w[VGG19_NUM_CONV]; /* [Cout][Cin][3][3] */
+    float *conv_b[VGG19_NUM_CONV]; /* [Cout] */
+    float *fc_w[VGG19_NUM_FC];     /* [Out][In] */
+    float *fc_b[VGG19_NUM_FC];     /* [Out] */
+} vgg19_params;
+
+const char *vgg_strerror(int status);
+
+/* Channel count rounded up to the granularity the convolution kernels read:
+ * one 64-byte row, i.e. a multiple of 16 for VGG_F32 and of 32 for VGG_BF16.
+ * Returns 0 for a bad dtype or C <= 0. */
+int vgg_padded_channels(int dtype, int C);
+
+/* ------------------------------------------------------------------ layout */
+
+/* Packs canonical fp32 weights [Cout][Cin][3][3] into the layout described
+ * above, converting to `dtype`.  With transpose_flip != 0 it instead writes
+ * the operand the data-gradient convolution consumes: element (t, ci, co) at
+ * (t*Cin + ci)*CoutP + co holding w[co][ci][8-t] (taps rotated by 180
+ * degrees, channel roles swapped; cf. the "reverse" ops of the backward
+ * column of the appendix table), CoutP = vgg_padded_channels(dtype, Cout). */
+int vgg_conv_pack_weights(int dtype, int Cin, int Cout, const float *w_oihw, void *w_packed,
+                          int transpose_flip, void *stream);
+/* Inverse of the forward packing for fp32 data (used for gradients and
+ * updated parameters): [9][Cout][CinP] fp32 -> [Cout][Cin][3][3] fp32. */
+int vgg_conv_unpack_weights(int Cin, int Cout, const float *w_packed, float *w_oihw, void *stream);
+
+/* fp32 NCHW -> `dtype` NHWC with the channel count padded with zeros to
+ * Cpad (Cpad >= C).  And back: `dtype` NHWC (channel stride Cpad) -> fp32
+ * NCHW keeping the first C channels. */
+int vgg_nchw_to_nhwc(int dtype, int N, int C, int H, int W, int Cpad, const float *x_nchw,
+                     void *y_nhwc, void *stream);
+int vgg_nhwc_to_nchw(int dtype, int N, int C, int H, int W, int Cpad, const void *x_nhwc,
+                     float *y_nchw, void *stream);
+/* Element-wise fp32 <-> dtype conversion of n elements (RNE for bf16). */
+int vgg_convert(int src_dtype, int dst_dtype, size_t n, const void *src, void *dst, void *stream);
+
+/* ------------------------------------------------------------- convolution */
+
+/* y[n,h,w,co] = f(bias[co] + sum_{kh,kw,ci} x[n,h+kh-1,w+kw-1,ci] * w[co,ci,kh,kw]),
+ * x = 0 outside the image, f = max(0,.) if relu else identity (appendix
+ * table rows "convolution", "add", "maximum": a cross-correlation, no kernel
+ * flip).  x is NHWC with exactly Cin channels, y NHWC with Cout channels,
+ * w_packed as produced by vgg_conv_pack_weights(transpose_flip = 0), bias
+ * fp32 [Cout] or NULL.  Workspace is only needed when Cin differs from
+ * vgg_padded_channels(dtype, Cin) (a zero-padded copy of x is made there). */
+size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
+int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x_nhwc,
+                    const void *w_packed, const float *bias, void *y_nhwc, int relu, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/* dx[n,h,w,ci] = sum_{kh,kw,co} g[n,h-kh+1,w-kw+1,co] * w[co,ci,kh,kw]
+ * (gradient with respect to the convolution's input; g is the gradient with
+ * respect to its pre-activation output, zero outside the image).  w_tf is
+ * the transpose_flip != 0 packing.  If relu_src is non-NULL it must be an
+ * NHWC tensor shaped like dx and dx is multiplied by (relu_src > 0), i.e.
+ * the ReLU backward of the layer that produced this convolution's input is
+ * fused in.  Workspace is only needed when Cout differs from
+ * vgg_padded_channels(dtype, Cout). */
+size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
+int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, const void *g_nhwc,
+                         const void *w_tf, const void *relu_src, void *dx_nhwc, void *ws,
+                         size_t ws_bytes, void *stream);
+
+/* dw[t,co,ci] = sum_{n,h,w} g[n,h,w,co] * x[n,h+kh-1,w+kw-1,ci],
+ * db[co] = sum_{n,h,w} g[n,h,w,co].  fp32 only.  dw is written in the packed
+ * layout [9][Cout][CinP] (padding entries zero), db is [Cout] or NULL; Cout
+ * must be a multiple of 4 (VGG_ERR_UNSUPPORTED otherwise).  The
+ * pixel sum is split over workgroups; partial sums go to ws and a second
+ * kernel adds them in a fixed order, so results are reproducible run to run. */
+size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
+int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, const void *x_nhwc,
+                           const void *g_nhwc, float *dw_packed, float *db, void *ws,
+                           size_t ws_bytes, void *stream);
+
+/* -------------------------------------------------------------------- pool */
+
+/* y[n,i,j,c] = max_{dh,dw in {0,1}} x[n,2i+dh,2j+dw,c] (appendix table row
+ * "reduce-window").  argmax (may be NULL) gets one byte per output element,
+ * 2*dh+dw of the first maximum in the order (0,0),(0,1),(1,0),(1,1).  H, W
+ * are the input sizes and must be even; C must be a multiple of 8. */
+int vgg_maxpool2x2(int dtype, int N, int H, int W, int C, const void *x_nhwc, void *y_nhwc,
+                   uint8_t *argmax, void *stream);
+/* Scatter backward (row "select-and-scatter"): dx gets dy at the argmax
+ * position of each window and zero at the other three.  H, W = size of dx. */
+int vgg_maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy_nhwc,
+                       const uint8_t *argmax, void *dx_nhwc, void *stream);
+
+/* ------------------------------------------------------------------- dense */
+
+/* z[n,o] = f(bias[o] + sum_i w[o,i] * a[n,i])  -- the paper's
+ * dense(W, x, b) = W*x + b applied to each image (listing "dense"; HLO
+ * "dot").  a [N][In] and w [Out][In] in `dtype`; z [N][Out] in z_dtype;
+ * In must be a multiple of 32.  The contraction is split over workgroups;
+ * partial sums go to ws and are added in a fixed order. */
+size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out);
+int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias,
+           void *z, int z_dtype, int relu, void *ws, size_t ws_bytes, void *stream);
+
+/* fp32 only.  dw[o,i] = sum_n dz[n,o] a[n,i]; db[o] = sum_n dz[n,o] (db may
+ * be NULL); if da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by
+ * (a[n,i] > 0) when relu_mask != 0 (ReLU backward of the producer of a). */
+size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out);
+int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz,
+               float *dw, float *db, void *da, int relu_mask, void *ws, size_t ws_bytes,
+               void *stream);
+
+/* ------------------------------------------------------ softmax, loss, SGD */
+
+/* p[n,k] = exp(z[n,k]) / sum_j exp(z[n,j]) per row (listing "softmax"),
+ * evaluated with the row maximum subtracted from the exponents. */
+int vgg_softmax(int N, int K, const float *z, float *p, void *stream);
+/* loss[0] = -(1/N) sum_n log p[n,labels[n]];  dz = (p - onehot(labels))/N.
+ * loss and dz may each be NULL.  Labels outside [0,K) contribute nothing
+ * (labels live on the device and cannot be validated on the host).  ws needs
+ * N floats when loss is requested (per-row terms, summed in a fixed order). */
+int vgg_softmax_xent_bwd(int N, int K, const float *p, const int32_t *labels, float *loss,
+                         float *dz, void *ws, size_t ws_bytes, void *stream);
+/* theta[i] -= lr * grad[i], i < n. */
+int vgg_sgd_update(size_t n, float *theta, const float *grad, float lr, void *stream);
+
+/* ------------------------------------------------------------- whole model */
+
+/* Size in bytes of the packed parameter block for cfg, and of the
+ * workspaces of the two model-level calls.  0 if cfg is invalid. */
+size_t vgg19_packed_bytes(const vgg_config *cfg);
+size_t vgg19_forward_workspace_bytes(const vgg_config *cfg);
+size_t vgg19_train_workspace_bytes(const vgg_config *cfg);
+
+/* canonical fp32 -> packed block (convolution weights packed and converted,
+ * the first dense layer's columns permuted from C,H,W to H,W,C order, biases
+ * fp32), and back (fp32 configs only). */
+int vgg19_pack_params(const vgg_config *cfg, const vgg19_params *canonical, void *packed,
+                      size_t packed_bytes, void *stream);
+int vgg19_unpack_params(const vgg_config *cfg, const void *packed, size_t packed_bytes,
+                        const vgg19_params *canonical_out, void *stream);
+
+/* Batch of images in, class scores and probabilities out (section "VGG19
+ * forward pass").  x_nchw fp32 [N][3][H][W]; logits and probs fp32
+ * [N][classes] (either may be NULL). */
+int vgg19_forward(const vgg_config *cfg, const float *x_nchw, const void *packed, float *logits,
+                  float *probs, void *ws, size_t ws_bytes, void *stream);
+
+/* One training step (section "VGG19 backward pass", with mean softmax
+ * cross-entropy in place of the paper's stand-in sum, whose gradient through
+ * softmax is identically zero): forward, loss, full backward, then
+ * theta <- theta - cfg->lr * grad on the packed block in place.  fp32
+ * configs only.  labels int32 [N].  grads_or_null, when given, receives the
+ * 38 gradient tensors in canonical layout.  loss (1 float) and logits
+ * ([N][classes]) may be NULL. */
+int vgg19_train_step(const vgg_config *cfg, const float *x_nchw, const int32_t *labels,
+                     void *packed_inout, size_t packed_bytes, const vgg19_params *grads_or_null,
+                     float *loss, float *logits, void *ws, size_t ws_bytes, void *stream);
+
+/* Launch plan of the two model-level calls, for inspection: writes up to
+ * `cap` kernel-kind codes into kinds_host (host memory) and returns how many
+ * launches the call makes (negative vgg_status on a bad cfg).  Codes:
+ * 1 conv fwd, 2 conv data-grad, 3 conv weight-grad, 4 pool, 5 pool bwd,
+ * 6 dense fwd, 7 dense bwd (dW), 8 dense bwd (dA), 9 other. */
+int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VGG_MI355X_H */

@@ -1,0 +1,644 @@
+// C ABI of libvgg_mi355x.so: argument validation on the host, then kernel
+// launches; plus the two model-level launch sequences (section "VGG19 forward
+// pass" / "VGG19 backward pass").
+#include "common.h"
+
+namespace vgg {
+// kernels' host launchers (defined in the other translation units)
+int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
+                  const void *mask, void *y, int relu, hipStream_t stream);
+size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
+int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
+                  hipStream_t stream);
+int maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *arg, hipStream_t s);
+int maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy, const uint8_t *arg, void *dx, hipStream_t s);
+int softmax_rows(int N, int K, const float *z, float *p, hipStream_t s);
+int softmax_xent_bwd(int N, int K, const float *p, const int32_t *labels, float *loss, float *dz, float *rowloss,
+                     hipStream_t s);
+int sgd_update(size_t n, float *theta, const float *grad, float lr, hipStream_t s);
+int nchw_to_nhwc(int dtype, int N, int C, int H, int W, int Cpad, const float *x, void *y, hipStream_t s);
+int nhwc_to_nchw(int dtype, int N, int C, int H, int W, int Cpad, const void *x, float *y, hipStream_t s);
+int pad_channels(int dtype, size_t pixels, int C, int Cpad, const void *x, void *y, hipStream_t s);
+int convert(int sd, int dd, size_t n, const void *src, void *dst, hipStream_t s);
+int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s);
+int flip_packed_w(int CinP, int Cout, int CoutP, const float *src, float *dst, hipStream_t s);
+int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s);
+int permute_fc_cols(int dst_dtype, int Out, int C, int HW, int to_hwc, const float *src, void *dst, hipStream_t s);
+size_t fc_workspace(int dtype, int N, int In, int Out);
+int fc_forward(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias, void *z, int z_dtype,
+               int relu, void *ws, hipStream_t s);
+size_t fc_bwd_workspace(int N, int In, int Out);
+int fc_backward(int N, int In, int Out, const float *a, const float *w, const float *dz, float *dw, float *db, float *da,
+                int relu_mask, void *ws, hipStream_t s);
+
+namespace {
+
+const int kConvCh[VGG19_NUM_CONV][2] = {{3, 64},    {64, 64},   {64, 128},  {128, 128}, {128, 256}, {256, 256},
+                                        {256, 256}, {256, 256}, {256, 512}, {512, 512}, {512, 512}, {512, 512},
+                                        {512, 512}, {512, 512}, {512, 512}, {512, 512}};
+inline bool pool_after(int l) { return l == 1 || l == 3 || l == 7 || l == 11 || l == 15; }
+
+bool cfg_ok(const vgg_config *c)
+{
+    return c && dtype_ok(c->dtype) && c->N > 0 && c->H > 0 && c->W > 0 && c->H % 32 == 0 && c->W % 32 == 0 &&
+           c->fc_hidden > 0 && c->fc_hidden % 32 == 0 && c->classes > 0 && c->flags == 0 &&
+           (long)c->N * c->H * c->W <= (1L << 27);
+}
+
+struct Bump {
+    size_t off = 0;
+    size_t take(size_t bytes) { const size_t o = off; off += round_up(bytes, 256); return o; }
+};
+
+// Offsets inside the packed parameter block.
+struct PackedLayout {
+    size_t conv_w[VGG19_NUM_CONV], conv_b[VGG19_NUM_CONV], fc_w[VGG19_NUM_FC], fc_b[VGG19_NUM_FC];
+    int cinp[VGG19_NUM_CONV];
+    int fc_in[VGG19_NUM_FC], fc_out[VGG19_NUM_FC];
+    size_t total;
+};
+
+PackedLayout packed_layout(const vgg_config *c)
+{
+    PackedLayout L;
+    Bump b;
+    const int es = dtype_size(c->dtype);
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+        L.cinp[l] = padded_channels(c->dtype, kConvCh[l][0]);
+        L.conv_w[l] = b.take((size_t)9 * kConvCh[l][1] * L.cinp[l] * es);
+    }
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) L.conv_b[l] = b.take((size_t)kConvCh[l][1] * 4);
+    const int flat = 512 * (c->H / 32) * (c->W / 32);
+    const int dims[4] = {flat, c->fc_hidden, c->fc_hidden, c->classes};
+    for (int l = 0; l < VGG19_NUM_FC; ++l) {
+        L.fc_in[l] = dims[l];
+        L.fc_out[l] = dims[l + 1];
+        L.fc_w[l] = b.take((size_t)dims[l] * dims[l + 1] * es);
+    }
+    for (int l = 0; l < VGG19_NUM_FC; ++l) L.fc_b[l] = b.take((size_t)dims[l + 1] * 4);
+    L.total = b.off;
+    return L;
+}
+
+// Workspace layout of the model-level calls.
+struct WsLayout {
+    size_t x0;                         // padded NHWC input
+    size_t act[VGG19_NUM_CONV];        // conv outputs (training: all kept; inference: ping-pong)
+    size_t pooled[VGG19_NUM_CONV];     // pool outputs (index = conv layer the pool follows)
+    size_t argmax[VGG19_NUM_CONV];
+    size_t z1, z2, logits, probs, fcws;
+    // training only
+    size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
+    size_t total;
+    int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
+};
+
+WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
+{
+    WsLayout L;
+    Bump b;
+    const size_t es = dtype_size(c->dtype);
+    const size_t N = c->N;
+    int h = c->H, w = c->W;
+    L.x0 = b.take(N * h * w * P.cinp[0] * es);
+    size_t max_act = 0;
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+        L.H[l] = h; L.W[l] = w;
+        const size_t a = N * h * w * kConvCh[l][1] * es;
+        if (a > max_act) max_act = a;
+        if (pool_after(l)) { h /= 2; w /= 2; }
+    }
+    if (training) {
+        for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            const size_t elems = N * L.H[l] * L.W[l] * kConvCh[l][1];
+            L.act[l] = b.take(elems * es);
+            L.pooled[l] = L.argmax[l] = 0;
+            if (pool_after(l)) {
+                L.pooled[l] = b.take(elems / 4 * es);
+                L.argmax[l] = b.take(elems / 4);
+            }
+        }
+    } else {
+        const size_t pA = b.take(max_act), pB = b.take(max_act);
+        // forward ping-pong: every op reads one buffer and writes the other
+        int cur = 0;
+        for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            L.act[l] = cur ? pB : pA; cur ^= 1;
+            L.pooled[l] = L.argmax[l] = 0;
+            if (pool_after(l)) { L.pooled[l] = cur ? pB : pA; cur ^= 1; }
+        }
+    }
+    L.z1 = b.take(N * c->fc_hidden * es);
+    L.z2 = b.take(N * c->fc_hidden * es);
+    L.logits = b.take(N * c->classes * 4);
+    L.probs = b.take(N * c->classes * 4);
+    size_t fw = 0;
+    for (int l = 0; l < VGG19_NUM_FC; ++l) {
+        const size_t s = fc_workspace(c->dtype, c->N, P.fc_in[l], P.fc_out[l]);
+        if (s > fw) fw = s;
+    }
+    L.fcws = b.take(fw);
+    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = 0;
+    if (training) {
+        L.dlogits = b.take(N * c->classes * 4);
+        L.dz2 = b.take(N * c->fc_hidden * 4);
+        L.dz1 = b.take(N * c->fc_hidden * 4);
+        L.gA = b.take(max_act);
+        L.gB = b.take(max_act);
+        L.wflip = b.take((size_t)9 * 512 * 512 * 4);
+        L.grads = b.take(P.total);
+        size_t wg = 0, fb = 0;
+        for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            const size_t s = conv3x3_wgrad_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
+            if (s > wg) wg = s;
+        }
+        for (int l = 0; l < VGG19_NUM_FC; ++l) {
+            const size_t s = fc_bwd_workspace(c->N, P.fc_in[l], P.fc_out[l]);
+            if (s > fb) fb = s;
+        }
+        L.wgws = b.take(wg);
+        L.fcbws = b.take(fb);
+        L.rowloss = b.take(N * 4);
+    }
+    L.total = b.off;
+    return L;
+}
+
+// Records the launch plan and, unless dry, stops at the first failing launch.
+struct Recorder {
+    int *kinds; int cap; int n; bool dry; int rc;
+    bool skip(int kind)
+    {
+        if (rc != VGG_OK) return true;
+        if (kinds && n < cap) kinds[n] = kind;
+        ++n;
+        return dry;
+    }
+};
+#define VGG_STEP(rec, kind, call) do { if (!(rec).skip(kind)) (rec).rc = (call); } while (0)
+
+enum { K_CONV = 1, K_DGRAD = 2, K_WGRAD = 3, K_POOL = 4, K_POOLB = 5, K_FC = 6, K_FCDW = 7, K_FCDA = 8, K_OTHER = 9 };
+
+void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, const float *x, const char *pk, float *logits,
+                 float *probs, bool want_probs, char *ws, bool training, hipStream_t s, Recorder &rec)
+{
+    const int dt = c->dtype, N = c->N;
+    VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, P.cinp[0], x, ws + L.x0, s));
+    const char *cur = ws + L.x0;
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+        char *out = ws + L.act[l];
+        VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
+                                           reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr, out, 1, s));
+        cur = out;
+        if (pool_after(l)) {
+            char *po = ws + L.pooled[l];
+            uint8_t *arg = training ? reinterpret_cast<uint8_t *>(ws + L.argmax[l]) : nullptr;
+            VGG_STEP(rec, K_POOL, maxpool2x2(dt, N, L.H[l], L.W[l], kConvCh[l][1], cur, po, arg, s));
+            cur = po;
+        }
+    }
+    float *lg = logits ? logits : reinterpret_cast<float *>(ws + L.logits);
+    VGG_STEP(rec, K_FC, fc_forward(dt, N, P.fc_in[0], P.fc_out[0], cur, pk + P.fc_w[0],
+                                   reinterpret_cast<const float *>(pk + P.fc_b[0]), ws + L.z1, dt, 1, ws + L.fcws, s));
+    VGG_STEP(rec, K_FC, fc_forward(dt, N, P.fc_in[1], P.fc_out[1], ws + L.z1, pk + P.fc_w[1],
+                                   reinterpret_cast<const float *>(pk + P.fc_b[1]), ws + L.z2, dt, 1, ws + L.fcws, s));
+    VGG_STEP(rec, K_FC, fc_forward(dt, N, P.fc_in[2], P.fc_out[2], ws + L.z2, pk + P.fc_w[2],
+                                   reinterpret_cast<const float *>(pk + P.fc_b[2]), lg, VGG_F32, 0, ws + L.fcws, s));
+    if (want_probs) {
+        float *pr = probs ? probs : reinterpret_cast<float *>(ws + L.probs);
+        VGG_STEP(rec, K_OTHER, softmax_rows(N, c->classes, lg, pr, s));
+    }
+}
+
+void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, const float *x, const int32_t *labels, char *pk,
+               const vgg19_params *grads_out, float *loss, float *logits, char *ws, hipStream_t s, Recorder &rec)
+{
+    const int N = c->N;
+    float *lg = logits ? logits : reinterpret_cast<float *>(ws + L.logits);
+    float *pr = reinterpret_cast<float *>(ws + L.probs);
+    run_forward(c, P, L, x, pk, lg, pr, true, ws, true, s, rec);
+    char *gr = ws + L.grads;  // gradient block, same layout as the packed parameters
+    auto F = [](char *p) { return reinterpret_cast<float *>(p); };
+    VGG_STEP(rec, K_OTHER, softmax_xent_bwd(N, c->classes, pr, labels, loss, F(ws + L.dlogits), F(ws + L.rowloss), s));
+    // dense layers, last to first; each data gradient is masked by (input > 0)
+    const char *fc_in[3] = {ws + L.pooled[15], ws + L.z1, ws + L.z2};
+    float *fc_dz[3] = {F(ws + L.dz1), F(ws + L.dz2), F(ws + L.dlogits)};
+    float *dflat = F(ws + L.gA);
+    for (int l = 2; l >= 0; --l) {
+        float *da = l == 0 ? dflat : fc_dz[l - 1];
+        if (!rec.skip(K_FCDW)) {
+            rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const float *>(fc_in[l]), F(pk + P.fc_w[l]),
+                                 fc_dz[l], F(gr + P.fc_w[l]), F(gr + P.fc_b[l]), da, 1, ws + L.fcbws, s);
+        }
+        rec.skip(K_FCDA);  // issued by the same call; listed for the plan
+    }
+    // convolution stack, last to first
+    char *gbuf[2] = {ws + L.gA, ws + L.gB};
+    int cur = 0;  // gbuf[cur] holds the gradient w.r.t. the output of layer l (after its pool, if any)
+    for (int l = VGG19_NUM_CONV - 1; l >= 0; --l) {
+        const int H = L.H[l], W = L.W[l], Cin = kConvCh[l][0], Cout = kConvCh[l][1];
+        if (pool_after(l)) {
+            VGG_STEP(rec, K_POOLB, maxpool2x2_bwd(VGG_F32, N, H, W, Cout, gbuf[cur],
+                                                  reinterpret_cast<const uint8_t *>(ws + L.argmax[l]), gbuf[cur ^ 1], s));
+            cur ^= 1;
+        }
+        const char *xin = l == 0 ? ws + L.x0 : (pool_after(l - 1) ? ws + L.pooled[l - 1] : ws + L.act[l - 1]);
+        VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, P.cinp[l], Cout, reinterpret_cast<const float *>(xin), F(gbuf[cur]),
+                                            F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
+        if (l > 0) {
+            // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
+            VGG_STEP(rec, K_OTHER, flip_packed_w(P.cinp[l], Cout, Cout, F(pk + P.conv_w[l]), F(ws + L.wflip), s));
+            VGG_STEP(rec, K_DGRAD, conv3x3_igemm(VGG_F32, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
+                                                gbuf[cur ^ 1], 0, s));
+            cur ^= 1;
+        }
+    }
+    if (grads_out) {
+        for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            VGG_STEP(rec, K_OTHER, unpack_conv_w(kConvCh[l][0], kConvCh[l][1], F(gr + P.conv_w[l]), grads_out->conv_w[l], s));
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, kConvCh[l][1], gr + P.conv_b[l], grads_out->conv_b[l], s));
+        }
+        VGG_STEP(rec, K_OTHER, permute_fc_cols(VGG_F32, P.fc_out[0], 512, P.fc_in[0] / 512, 0, F(gr + P.fc_w[0]),
+                                               grads_out->fc_w[0], s));
+        for (int l = 1; l < VGG19_NUM_FC; ++l)
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, (size_t)P.fc_in[l] * P.fc_out[l], gr + P.fc_w[l], grads_out->fc_w[l], s));
+        for (int l = 0; l < VGG19_NUM_FC; ++l)
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], gr + P.fc_b[l], grads_out->fc_b[l], s));
+    }
+    VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
+}
+
+bool params_ok(const vgg19_params *p)
+{
+    if (!p) return false;
+    for (int l = 0; l < VGG19_NUM_CONV; ++l)
+        if (!p->conv_w[l] || !p->conv_b[l]) return false;
+    for (int l = 0; l < VGG19_NUM_FC; ++l)
+        if (!p->fc_w[l] || !p->fc_b[l]) return false;
+    return true;
+}
+bool params_aligned(const vgg19_params *p)
+{
+    for (int l = 0; l < VGG19_NUM_CONV; ++l)
+        if (!aligned16(p->conv_w[l]) || !aligned16(p->conv_b[l])) return false;
+    for (int l = 0; l < VGG19_NUM_FC; ++l)
+        if (!aligned16(p->fc_w[l]) || !aligned16(p->fc_b[l])) return false;
+    return true;
+}
+
+bool conv_shape_ok(int N, int H, int W, int Cin, int Cout)
+{
+    return N > 0 && H > 0 && W > 0 && Cin > 0 && Cout > 0 && (long)N * H * W <= (1L << 27) &&
+           (long)N * H * W * (long)(Cin > Cout ? Cin : Cout) <= (1L << 33);
+}
+
+}  // namespace
+}  // namespace vgg
+
+using namespace vgg;
+
+extern "C" {
+
+const char *vgg_strerror(int status)
+{
+    switch (status) {
+    case VGG_OK: return "ok";
+    case VGG_ERR_NULL: return "null pointer";
+    case VGG_ERR_SHAPE: return "bad shape";
+    case VGG_ERR_DTYPE: return "bad dtype";
+    case VGG_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case VGG_ERR_WORKSPACE: return "workspace missing or too small";
+    case VGG_ERR_LAUNCH: return "kernel launch failed";
+    case VGG_ERR_UNSUPPORTED: return "unsupported request";
+    default: return "unknown status";
+    }
+}
+
+int vgg_padded_channels(int dtype, int C) { return (C > 0 && dtype_ok(dtype)) ? padded_channels(dtype, C) : 0; }
+
+int vgg_conv_pack_weights(int dtype, int Cin, int Cout, const float *w_oihw, void *w_packed, int transpose_flip, void *stream)
+{
+    if (!w_oihw || !w_packed) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (Cin <= 0 || Cout <= 0) return VGG_ERR_SHAPE;
+    if (!aligned16(w_oihw) || !aligned16(w_packed)) return VGG_ERR_ALIGN;
+    return pack_conv_w(dtype, Cin, Cout, w_oihw, w_packed, transpose_flip ? 1 : 0, (hipStream_t)stream);
+}
+
+int vgg_conv_unpack_weights(int Cin, int Cout, const float *w_packed, float *w_oihw, void *stream)
+{
+    if (!w_oihw || !w_packed) return VGG_ERR_NULL;
+    if (Cin <= 0 || Cout <= 0) return VGG_ERR_SHAPE;
+    if (!aligned16(w_oihw) || !aligned16(w_packed)) return VGG_ERR_ALIGN;
+    return unpack_conv_w(Cin, Cout, w_packed, w_oihw, (hipStream_t)stream);
+}
+
+int vgg_nchw_to_nhwc(int dtype, int N, int C, int H, int W, int Cpad, const float *x, void *y, void *stream)
+{
+    if (!x || !y) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || Cpad < C) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return VGG_ERR_ALIGN;
+    return nchw_to_nhwc(dtype, N, C, H, W, Cpad, x, y, (hipStream_t)stream);
+}
+
+int vgg_nhwc_to_nchw(int dtype, int N, int C, int H, int W, int Cpad, const void *x, float *y, void *stream)
+{
+    if (!x || !y) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || Cpad < C) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return VGG_ERR_ALIGN;
+    return nhwc_to_nchw(dtype, N, C, H, W, Cpad, x, y, (hipStream_t)stream);
+}
+
+int vgg_convert(int sd, int dd, size_t n, const void *src, void *dst, void *stream)
+{
+    if (!src || !dst) return VGG_ERR_NULL;
+    if (!dtype_ok(sd) || !dtype_ok(dd)) return VGG_ERR_DTYPE;
+    if (n == 0) return VGG_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return VGG_ERR_ALIGN;
+    return convert(sd, dd, n, src, dst, (hipStream_t)stream);
+}
+
+size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)
+{
+    if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
+    const int cp = padded_channels(dtype, Cin);
+    return cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+}
+
+int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
+                    void *y, int relu, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!x || !w || !y) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (!conv_shape_ok(N, H, W, Cin, Cout)) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
+    const size_t need = vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout);
+    if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
+    const int cp = padded_channels(dtype, Cin);
+    hipStream_t s = (hipStream_t)stream;
+    if (need) {
+        const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, ws, s);
+        if (rc) return rc;
+        x = ws;
+    }
+    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, relu ? 1 : 0, s);
+}
+
+size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)
+{
+    if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
+    const int cp = padded_channels(dtype, Cout);
+    return cp == Cout ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+}
+
+int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, const void *g, const void *w_tf,
+                         const void *relu_src, void *dx, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!g || !w_tf || !dx) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (!conv_shape_ok(N, H, W, Cin, Cout)) return VGG_ERR_SHAPE;
+    if (!aligned16(g) || !aligned16(w_tf) || !aligned16(dx) || (relu_src && !aligned16(relu_src)) || (ws && !aligned16(ws)))
+        return VGG_ERR_ALIGN;
+    const size_t need = vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout);
+    if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
+    const int cp = padded_channels(dtype, Cout);
+    hipStream_t s = (hipStream_t)stream;
+    if (need) {
+        const int rc = pad_channels(dtype, (size_t)N * H * W, Cout, cp, g, ws, s);
+        if (rc) return rc;
+        g = ws;
+    }
+    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, 0, s);
+}
+
+size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)
+{
+    if (dtype != VGG_F32 || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
+    const int cp = padded_channels(dtype, Cin);
+    size_t pad = cp == Cin ? 0 : round_up((size_t)N * H * W * cp * 4, 256);
+    return pad + conv3x3_wgrad_workspace(N, H, W, cp, Cout);
+}
+
+int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *g, float *dw,
+                           float *db, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!x || !g || !dw) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (!conv_shape_ok(N, H, W, Cin, Cout)) return VGG_ERR_SHAPE;
+    if (Cout % 4) return VGG_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(dw) || (db && !aligned16(db)) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
+    const size_t need = vgg_conv3x3_bwd_weight_workspace_bytes(dtype, N, H, W, Cin, Cout);
+    if (!ws || ws_bytes < need) return VGG_ERR_WORKSPACE;
+    const int cp = padded_channels(dtype, Cin);
+    hipStream_t s = (hipStream_t)stream;
+    char *wsp = static_cast<char *>(ws);
+    if (cp != Cin) {
+        const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, wsp, s);
+        if (rc) return rc;
+        x = wsp;
+        wsp += round_up((size_t)N * H * W * cp * 4, 256);
+    }
+    return conv3x3_wgrad(N, H, W, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp, s);
+}
+
+int vgg_maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *argmax, void *stream)
+{
+    if (!x || !y) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || C % 8) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return VGG_ERR_ALIGN;
+    return maxpool2x2(dtype, N, H, W, C, x, y, argmax, (hipStream_t)stream);
+}
+
+int vgg_maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy, const uint8_t *argmax, void *dx, void *stream)
+{
+    if (!dy || !argmax || !dx) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || C % 8) return VGG_ERR_SHAPE;
+    if (!aligned16(dy) || !aligned16(dx)) return VGG_ERR_ALIGN;
+    return maxpool2x2_bwd(dtype, N, H, W, C, dy, argmax, dx, (hipStream_t)stream);
+}
+
+size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out)
+{
+    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
+    return fc_workspace(dtype, N, In, Out);
+}
+
+int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias, void *z, int z_dtype, int relu,
+           void *ws, size_t ws_bytes, void *stream)
+{
+    if (!a || !w || !z) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype) || !dtype_ok(z_dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(z) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
+    if (!ws || ws_bytes < fc_workspace(dtype, N, In, Out)) return VGG_ERR_WORKSPACE;
+    return fc_forward(dtype, N, In, Out, a, w, bias, z, z_dtype, relu ? 1 : 0, ws, (hipStream_t)stream);
+}
+
+size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out)
+{
+    if (dtype != VGG_F32 || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
+    return fc_bwd_workspace(N, In, Out);
+}
+
+int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz, float *dw, float *db, void *da,
+               int relu_mask, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!a || !w || !dz || !dw) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(dz) || !aligned16(dw) || (da && !aligned16(da)) || (ws && !aligned16(ws)))
+        return VGG_ERR_ALIGN;
+    if (da && (!ws || ws_bytes < fc_bwd_workspace(N, In, Out))) return VGG_ERR_WORKSPACE;
+    return fc_backward(N, In, Out, static_cast<const float *>(a), static_cast<const float *>(w), static_cast<const float *>(dz),
+                       dw, db, static_cast<float *>(da), relu_mask ? 1 : 0, ws, (hipStream_t)stream);
+}
+
+int vgg_softmax(int N, int K, const float *z, float *p, void *stream)
+{
+    if (!z || !p) return VGG_ERR_NULL;
+    if (N <= 0 || K <= 0) return VGG_ERR_SHAPE;
+    return softmax_rows(N, K, z, p, (hipStream_t)stream);
+}
+
+int vgg_softmax_xent_bwd(int N, int K, const float *p, const int32_t *labels, float *loss, float *dz, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    if (!p || !labels) return VGG_ERR_NULL;
+    if (N <= 0 || K <= 0) return VGG_ERR_SHAPE;
+    if (loss && (!ws || ws_bytes < (size_t)N * 4)) return VGG_ERR_WORKSPACE;
+    return softmax_xent_bwd(N, K, p, labels, loss, dz, static_cast<float *>(ws), (hipStream_t)stream);
+}
+
+int vgg_sgd_update(size_t n, float *theta, const float *grad, float lr, void *stream)
+{
+    if (!theta || !grad) return VGG_ERR_NULL;
+    if (n == 0) return VGG_ERR_SHAPE;
+    if (!aligned16(theta) || !aligned16(grad)) return VGG_ERR_ALIGN;
+    return sgd_update(n, theta, grad, lr, (hipStream_t)stream);
+}
+
+size_t vgg19_packed_bytes(const vgg_config *cfg) { return cfg_ok(cfg) ? packed_layout(cfg).total : 0; }
+
+size_t vgg19_forward_workspace_bytes(const vgg_config *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return ws_layout(cfg, packed_layout(cfg), false).total;
+}
+
+size_t vgg19_train_workspace_bytes(const vgg_config *cfg)
+{
+    if (!cfg_ok(cfg) || cfg->dtype != VGG_F32) return 0;
+    return ws_layout(cfg, packed_layout(cfg), true).total;
+}
+
+int vgg19_pack_params(const vgg_config *cfg, const vgg19_params *canon, void *packed, size_t packed_bytes, void *stream)
+{
+    if (!cfg || !canon || !packed) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (!params_ok(canon)) return VGG_ERR_NULL;
+    if (!aligned16(packed) || !params_aligned(canon)) return VGG_ERR_ALIGN;
+    const PackedLayout P = packed_layout(cfg);
+    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *pk = static_cast<char *>(packed);
+    int rc = VGG_OK;
+    for (int l = 0; l < VGG19_NUM_CONV && !rc; ++l) {
+        rc = pack_conv_w(cfg->dtype, kConvCh[l][0], kConvCh[l][1], canon->conv_w[l], pk + P.conv_w[l], 0, s);
+        if (!rc) rc = convert(VGG_F32, VGG_F32, kConvCh[l][1], canon->conv_b[l], pk + P.conv_b[l], s);
+    }
+    if (!rc) rc = permute_fc_cols(cfg->dtype, P.fc_out[0], 512, P.fc_in[0] / 512, 1, canon->fc_w[0], pk + P.fc_w[0], s);
+    for (int l = 1; l < VGG19_NUM_FC && !rc; ++l)
+        rc = convert(VGG_F32, cfg->dtype, (size_t)P.fc_in[l] * P.fc_out[l], canon->fc_w[l], pk + P.fc_w[l], s);
+    for (int l = 0; l < VGG19_NUM_FC && !rc; ++l) rc = convert(VGG_F32, VGG_F32, P.fc_out[l], canon->fc_b[l], pk + P.fc_b[l], s);
+    return rc;
+}
+
+int vgg19_unpack_params(const vgg_config *cfg, const void *packed, size_t packed_bytes, const vgg19_params *out, void *stream)
+{
+    if (!cfg || !out || !packed) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (!params_ok(out)) return VGG_ERR_NULL;
+    if (!aligned16(packed) || !params_aligned(out)) return VGG_ERR_ALIGN;
+    const PackedLayout P = packed_layout(cfg);
+    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const char *pk = static_cast<const char *>(packed);
+    int rc = VGG_OK;
+    for (int l = 0; l < VGG19_NUM_CONV && !rc; ++l) {
+        rc = unpack_conv_w(kConvCh[l][0], kConvCh[l][1], reinterpret_cast<const float *>(pk + P.conv_w[l]), out->conv_w[l], s);
+        if (!rc) rc = convert(VGG_F32, VGG_F32, kConvCh[l][1], pk + P.conv_b[l], out->conv_b[l], s);
+    }
+    if (!rc)
+        rc = permute_fc_cols(VGG_F32, P.fc_out[0], 512, P.fc_in[0] / 512, 0, reinterpret_cast<const float *>(pk + P.fc_w[0]),
+                             out->fc_w[0], s);
+    for (int l = 1; l < VGG19_NUM_FC && !rc; ++l)
+        rc = convert(VGG_F32, VGG_F32, (size_t)P.fc_in[l] * P.fc_out[l], pk + P.fc_w[l], out->fc_w[l], s);
+    for (int l = 0; l < VGG19_NUM_FC && !rc; ++l) rc = convert(VGG_F32, VGG_F32, P.fc_out[l], pk + P.fc_b[l], out->fc_b[l], s);
+    return rc;
+}
+
+int vgg19_forward(const vgg_config *cfg, const float *x, const void *packed, float *logits, float *probs, void *ws,
+                  size_t ws_bytes, void *stream)
+{
+    if (!cfg || !x || !packed) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(packed) || (logits && !aligned16(logits)) || (probs && !aligned16(probs)) ||
+        (ws && !aligned16(ws)))
+        return VGG_ERR_ALIGN;
+    const PackedLayout P = packed_layout(cfg);
+    const WsLayout L = ws_layout(cfg, P, false);
+    if (!ws || ws_bytes < L.total) return VGG_ERR_WORKSPACE;
+    Recorder rec{nullptr, 0, 0, false, VGG_OK};
+    run_forward(cfg, P, L, x, static_cast<const char *>(packed), logits, probs, probs != nullptr, static_cast<char *>(ws),
+                false, (hipStream_t)stream, rec);
+    return rec.rc;
+}
+
+int vgg19_train_step(const vgg_config *cfg, const float *x, const int32_t *labels, void *packed, size_t packed_bytes,
+                     const vgg19_params *grads, float *loss, float *logits, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!cfg || !x || !labels || !packed) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (grads && !params_ok(grads)) return VGG_ERR_NULL;
+    if (!aligned16(x) || !aligned16(packed) || (logits && !aligned16(logits)) || (ws && !aligned16(ws)) ||
+        (grads && !params_aligned(grads)))
+        return VGG_ERR_ALIGN;
+    const PackedLayout P = packed_layout(cfg);
+    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    const WsLayout L = ws_layout(cfg, P, true);
+    if (!ws || ws_bytes < L.total) return VGG_ERR_WORKSPACE;
+    Recorder rec{nullptr, 0, 0, false, VGG_OK};
+    run_train(cfg, P, L, x, labels, static_cast<char *>(packed), grads, loss, logits, static_cast<char *>(ws),
+              (hipStream_t)stream, rec);
+    return rec.rc;
+}
+
+int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap)
+{
+    if (!cfg) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (training && cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    const PackedLayout P = packed_layout(cfg);
+    const WsLayout L = ws_layout(cfg, P, training != 0);
+    Recorder rec{kinds_host, kinds_host ? cap : 0, 0, true, VGG_OK};
+    if (training)
+        run_train(cfg, P, L, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, rec);
+    else
+        run_forward(cfg, P, L, nullptr, nullptr, nullptr, nullptr, true, nullptr, false, nullptr, rec);
+    return rec.n;
+}
+
+}  // extern "C"

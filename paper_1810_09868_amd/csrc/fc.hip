@@ -1,0 +1,398 @@
+// Dense layers on MFMA for gfx950: z = a * W^T + b (the paper's
+// dense(W, x, b) = W*x + b, listing "dense", HLO "dot") and its two backward
+// products.  At batch ~100 these are weight-streaming problems: every weight
+// is read from HBM exactly once and the batch rows are the MFMA's M side.
+#include "common.h"
+
+namespace vgg {
+
+constexpr int kFcRow = 80;  // LDS row: 64 data bytes + 16 pad (same fragment format as the convolution)
+
+template <typename T> struct FcMma;
+template <> struct FcMma<float> {
+    static __device__ __forceinline__ void run(f32x16 &acc, const uint4 &a, const uint4 &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+    }
+};
+template <> struct FcMma<bf16_t> {
+    static __device__ __forceinline__ void run(f32x16 &acc, const uint4 &a, const uint4 &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                      __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    }
+};
+
+// Four consecutive floats row[c..c+3] with zeros at and beyond column C.  The
+// vector path needs the row to be 16-byte aligned (C a multiple of 4).
+__device__ __forceinline__ uint4 load_row4(const float *row, int c, int C, bool vec)
+{
+    if (vec && c + 3 < C) return *reinterpret_cast<const uint4 *>(row + c);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (c < C) v.x = __float_as_uint(row[c]);
+    if (c + 1 < C) v.y = __float_as_uint(row[c + 1]);
+    if (c + 2 < C) v.z = __float_as_uint(row[c + 2]);
+    if (c + 3 < C) v.w = __float_as_uint(row[c + 3]);
+    return v;
+}
+
+// ------------------------------------------------------------------ forward
+// Workgroup: 128 batch rows x 128 outputs x a range of 64-byte K units.
+// Wave w owns outputs [32w, 32w+32) and all four 32-row blocks.  The
+// activations of a step (4 units = 256 bytes per row) go through LDS; each
+// weight fragment is read straight from global memory by the one lane that
+// needs it (a weight is used by exactly one wave).
+struct FcArgs {
+    const char *a;   // [N][In]
+    const char *w;   // [Out][In]
+    float *part;     // [splits][N][Out]
+    int N, In, Out;
+    int units;            // In * sizeof(T) / 64
+    int units_per_split;
+    int tiles_n;          // column tiles
+    int tiles_m;          // row tiles
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
+{
+    __shared__ __align__(16) char As[4 * 128 * kFcRow];  // [unit][row][80]
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, khalf = lane >> 5;
+    int b = blockIdx.x;
+    const int tn = b % p.tiles_n; b /= p.tiles_n;
+    const int tm = b % p.tiles_m; b /= p.tiles_m;
+    const int split = b;
+    const int row0 = tm * 128, o0 = tn * 128;
+    const int u_begin = split * p.units_per_split;
+    const int u_end = min(u_begin + p.units_per_split, p.units);
+    const size_t rowbytes = (size_t)p.In * sizeof(T);
+
+    const int ocol = o0 + wv * 32 + r;
+    const bool ook = ocol < p.Out;
+    const char *wrow = p.w + (size_t)(ook ? ocol : 0) * rowbytes + khalf * 16;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+    for (int u0 = u_begin; u0 < u_end; u0 += 4) {
+        const int nu = min(4, u_end - u0);
+        // weight fragments for this step: nu units x 2 k-groups
+        uint4 bf[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                bf[u][g] = make_uint4(0, 0, 0, 0);
+                if (u < nu && ook)
+                    bf[u][g] = *reinterpret_cast<const uint4 *>(wrow + (size_t)(u0 + u) * 64 + g * 32);
+            }
+        __syncthreads();
+        for (int idx = tid; idx < 4 * 128 * 4; idx += 256) {
+            const int seg = idx & 3, row = (idx >> 2) & 127, u = idx >> 9;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (u < nu && row0 + row < p.N)
+                v = *reinterpret_cast<const uint4 *>(p.a + (size_t)(row0 + row) * rowbytes + (size_t)(u0 + u) * 64 + seg * 16);
+            *reinterpret_cast<uint4 *>(As + (u * 128 + row) * kFcRow + seg * 16) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 af = *reinterpret_cast<const uint4 *>(As + (u * 128 + i * 32 + r) * kFcRow + g * 32 + khalf * 16);
+                    FcMma<T>::run(acc[i], af, bf[u][g]);
+                }
+    }
+    if (ook) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = row0 + i * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                if (row < p.N) p.part[((size_t)split * p.N + row) * p.Out + ocol] = acc[i][e];
+            }
+    }
+}
+
+// z = f(bias + sum over splits), converted to TZ.
+template <typename TZ>
+__global__ void fc_finish_kernel(const float *__restrict__ part, const float *__restrict__ bias, TZ *__restrict__ z, int N,
+                                 int Out, int splits, int relu)
+{
+    const size_t n = (size_t)N * Out;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = bias ? bias[i % Out] : 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(size_t)k * n + i];
+    if (relu) s = fmaxf(s, 0.f);
+    Elem<TZ>::store(z + i, s);
+}
+
+static void fc_plan(int dtype, int N, int In, int Out, FcArgs &a)
+{
+    a.N = N; a.In = In; a.Out = Out;
+    a.units = In * dtype_size(dtype) / 64;
+    a.tiles_n = (Out + 127) / 128;
+    a.tiles_m = (N + 127) / 128;
+    const int tiles = a.tiles_n * a.tiles_m;
+    int splits = (512 + tiles - 1) / tiles;
+    const int max_splits = (a.units + 7) / 8;  // at least two steps per split
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    a.units_per_split = ((a.units + splits - 1) / splits + 3) / 4 * 4;
+}
+
+static int fc_splits(const FcArgs &a) { return (a.units + a.units_per_split - 1) / a.units_per_split; }
+
+size_t fc_workspace(int dtype, int N, int In, int Out)
+{
+    FcArgs a;
+    fc_plan(dtype, N, In, Out, a);
+    return round_up((size_t)fc_splits(a) * N * Out * 4, 256);
+}
+
+int fc_forward(int dtype, int N, int In, int Out, const void *a_, const void *w, const float *bias, void *z, int z_dtype,
+               int relu, void *ws, hipStream_t s)
+{
+    FcArgs a;
+    fc_plan(dtype, N, In, Out, a);
+    const int splits = fc_splits(a);
+    a.a = static_cast<const char *>(a_);
+    a.w = static_cast<const char *>(w);
+    a.part = static_cast<float *>(ws);
+    const dim3 grid((unsigned)(a.tiles_n * a.tiles_m * splits));
+    if (dtype == VGG_BF16)
+        hipLaunchKernelGGL(fc_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(fc_fwd_kernel<float>, grid, dim3(256), 0, s, a);
+    if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
+    const size_t n = (size_t)N * Out;
+    const dim3 g2((unsigned)((n + 255) / 256));
+    if (z_dtype == VGG_BF16)
+        hipLaunchKernelGGL(fc_finish_kernel<bf16_t>, g2, dim3(256), 0, s, a.part, bias, (bf16_t *)z, N, Out, splits, relu);
+    else
+        hipLaunchKernelGGL(fc_finish_kernel<float>, g2, dim3(256), 0, s, a.part, bias, (float *)z, N, Out, splits, relu);
+    return launch_status();
+}
+
+// ------------------------------------------------- backward: dW = dz^T * a
+// fp32.  Workgroup: 128 (o) x 128 (i) block of dW; the batch is the
+// contraction index, staged through LDS 64 rows at a time.  Wave (wo, wi)
+// owns a 64x64 sub-block = 2x2 MFMA tiles.
+__global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a, const float *__restrict__ dz,
+                                                    float *__restrict__ dw, int N, int In, int Out)
+{
+    constexpr int ROW = 128 * 4 + 16;
+    __shared__ __align__(16) char Ds[64 * ROW];
+    __shared__ __align__(16) char As[64 * ROW];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, kp = lane >> 5;
+    const int wo = wv & 1, wi = wv >> 1;
+    const int tiles_i = (In + 127) / 128;
+    const int i0 = (blockIdx.x % tiles_i) * 128, o0 = (blockIdx.x / tiles_i) * 128;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[x][y][e] = 0.f;
+
+    for (int n0 = 0; n0 < N; n0 += 64) {
+        __syncthreads();
+        for (int idx = tid; idx < 64 * 32; idx += 256) {
+            const int seg = idx & 31, row = idx >> 5;
+            uint4 vd = make_uint4(0, 0, 0, 0), va = make_uint4(0, 0, 0, 0);
+            if (n0 + row < N) {
+                vd = load_row4(dz + (size_t)(n0 + row) * Out, o0 + seg * 4, Out, (Out & 3) == 0);
+                va = load_row4(a + (size_t)(n0 + row) * In, i0 + seg * 4, In, (In & 3) == 0);
+            }
+            *reinterpret_cast<uint4 *>(Ds + row * ROW + seg * 16) = vd;
+            *reinterpret_cast<uint4 *>(As + row * ROW + seg * 16) = va;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int s = 0; s < 32; ++s) {
+            const int n = 2 * s + kp;
+            float af[2], bf[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) af[x] = *reinterpret_cast<const float *>(Ds + n * ROW + (wo * 64 + x * 32 + r) * 4);
+#pragma unroll
+            for (int y = 0; y < 2; ++y) bf[y] = *reinterpret_cast<const float *>(As + n * ROW + (wi * 64 + y * 32 + r) * 4);
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[x], bf[y], acc[x][y], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) {
+            const int i = i0 + wi * 64 + y * 32 + r;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+                if (o < Out && i < In) dw[(size_t)o * In + i] = acc[x][y][e];
+            }
+        }
+}
+
+// db[o] = sum_n dz[n][o]
+__global__ void fc_db_kernel(const float *__restrict__ dz, float *__restrict__ db, int N, int Out)
+{
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= Out) return;
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dz[(size_t)n * Out + o];
+    db[o] = s;
+}
+
+// --------------------------------------------------- backward: da = dz * W
+// fp32.  Workgroup: 128 batch rows x 256 inputs x a range of outputs (the
+// contraction index).  Wave (wr, wc) owns rows [64wr, 64wr+64) and the 128
+// inputs [128wc, 128wc+128).  A lane loads four consecutive inputs of one
+// weight row with one 16-byte load and feeds them to four different MFMA
+// column tiles, so accumulator tile j of lane r holds input 4r+j of the
+// wave's 128: the stores are 16-byte vectors as well.
+struct FcDaArgs {
+    const float *dz;  // [N][Out]
+    const float *w;   // [Out][In]
+    float *part;      // [splits][N][In]
+    int N, In, Out;
+    int tiles_i, tiles_m, o_per_split;
+};
+
+__global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
+{
+    __shared__ __align__(16) char Ds[128 * kFcRow];  // dz rows, 16 outputs per chunk
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, khalf = lane >> 5;
+    const int wr = wv & 1, wc = wv >> 1;
+    int b = blockIdx.x;
+    const int ti = b % p.tiles_i; b /= p.tiles_i;
+    const int tm = b % p.tiles_m; b /= p.tiles_m;
+    const int split = b;
+    const int row0 = tm * 128;
+    const int icol = ti * 256 + wc * 128 + 4 * r;  // first of this lane's 4 inputs
+    const bool iok = icol < p.In;                  // In is a multiple of 4
+    const int o_begin = split * p.o_per_split, o_end = min(o_begin + p.o_per_split, p.Out);
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[x][j][e] = 0.f;
+
+    for (int oc = o_begin; oc < o_end; oc += 16) {
+        __syncthreads();
+        for (int idx = tid; idx < 128 * 4; idx += 256) {
+            const int seg = idx & 3, row = idx >> 2;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row0 + row < p.N)
+                v = load_row4(p.dz + (size_t)(row0 + row) * p.Out, oc + seg * 4, o_end, (p.Out & 3) == 0);
+            *reinterpret_cast<uint4 *>(Ds + row * kFcRow + seg * 16) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            // this lane's four contraction indices: oc + 8g + 4*khalf + e
+            f32x4 wv4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int o = oc + g * 8 + khalf * 4 + e;
+                wv4[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (iok && o < o_end) wv4[e] = *reinterpret_cast<const f32x4 *>(p.w + (size_t)o * p.In + icol);
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const f32x4 af = *reinterpret_cast<const f32x4 *>(Ds + (wr * 64 + x * 32 + r) * kFcRow + g * 32 + khalf * 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[x][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], wv4[e][j], acc[x][j], 0, 0, 0);
+            }
+        }
+    }
+    if (iok) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = row0 + wr * 64 + x * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                if (row < p.N) {
+                    const f32x4 v = {acc[x][0][e], acc[x][1][e], acc[x][2][e], acc[x][3][e]};
+                    *reinterpret_cast<f32x4 *>(p.part + ((size_t)split * p.N + row) * p.In + icol) = v;
+                }
+            }
+    }
+}
+
+// da = (sum over splits) [* (a > 0)]
+template <typename T>
+__global__ void fc_da_finish_kernel(const float *__restrict__ part, const T *__restrict__ a, T *__restrict__ da, size_t n,
+                                    int splits, int relu_mask)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(size_t)k * n + i];
+    if (relu_mask && !(Elem<T>::load(a + i) > 0.f)) s = 0.f;
+    Elem<T>::store(da + i, s);
+}
+
+static void fc_da_plan(int N, int In, int Out, FcDaArgs &a)
+{
+    a.N = N; a.In = In; a.Out = Out;
+    a.tiles_i = (In + 255) / 256;
+    a.tiles_m = (N + 127) / 128;
+    const int tiles = a.tiles_i * a.tiles_m;
+    int splits = (512 + tiles - 1) / tiles;
+    const int max_splits = (Out + 63) / 64;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    a.o_per_split = ((Out + splits - 1) / splits + 15) / 16 * 16;
+}
+static int fc_da_splits(const FcDaArgs &a) { return (a.Out + a.o_per_split - 1) / a.o_per_split; }
+
+size_t fc_bwd_workspace(int N, int In, int Out)
+{
+    FcDaArgs a;
+    fc_da_plan(N, In, Out, a);
+    return round_up((size_t)fc_da_splits(a) * N * In * 4, 256);
+}
+
+int fc_backward(int N, int In, int Out, const float *a, const float *w, const float *dz, float *dw, float *db, float *da,
+                int relu_mask, void *ws, hipStream_t s)
+{
+    const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
+    hipLaunchKernelGGL(fc_dw_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out);
+    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
+    if (da) {
+        FcDaArgs p;
+        fc_da_plan(N, In, Out, p);
+        const int splits = fc_da_splits(p);
+        p.dz = dz; p.w = w; p.part = static_cast<float *>(ws);
+        hipLaunchKernelGGL(fc_da_kernel, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
+        const size_t n = (size_t)N * In;
+        hipLaunchKernelGGL(fc_da_finish_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.part, a, da, n,
+                           splits, relu_mask);
+    }
+    return launch_status();
+}
+
+}  // namespace vgg

@@ -1,0 +1,42 @@
+"""Helpers for the GPU parity tests: device upload, layout plumbing (torch is
+used only to hold and permute buffers) and the error metric."""
+import numpy as np
+import torch
+
+from paper_1810_09868_amd import binding as B
+
+TOL = {B.F32: 1e-4, B.BF16: 2e-2}
+TDT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def to_nhwc(x_nchw: np.ndarray, dtype: int) -> torch.Tensor:
+    """fp32 NCHW numpy -> device NHWC tensor of the library dtype, via the library's own converter."""
+    N, C, H, W = x_nchw.shape
+    src = dev(x_nchw.astype(np.float32))
+    out = torch.empty((N, H, W, C), dtype=TDT[dtype], device="cuda")
+    B.vgg_nchw_to_nhwc(dtype, N, C, H, W, C, src, out)
+    return out
+
+
+def from_nhwc(t: torch.Tensor) -> np.ndarray:
+    return t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy().astype(np.float64)
+
+
+def max_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |got_i - ref_i| / max_i |ref_i|  (element-wise relative error is undefined at the
+    zeros ReLU and pooling produce)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all()
+    scale = np.abs(ref).max()
+    return float(np.abs(got - ref).max() / (scale if scale > 0 else 1.0))
+
+
+def ws_bytes(n: int) -> torch.Tensor:
+    return torch.empty((max(int(n), 16),), dtype=torch.uint8, device="cuda")

@@ -1,0 +1,101 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and its
+launch plan has the structure the paper's instruction counts imply."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1810_09868_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vgg_mi355x.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(vgg(?:19)?_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared()
+    assert len(names) >= 28
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror_and_padded_channels():
+    L = B.lib()
+    assert L.vgg_strerror(0) == b"ok"
+    for code in range(-7, 0):
+        assert L.vgg_strerror(code) not in (b"ok", b"unknown status")
+    assert B.vgg_padded_channels(B.F32, 3) == 16
+    assert B.vgg_padded_channels(B.BF16, 3) == 32
+    assert B.vgg_padded_channels(B.BF16, 64) == 64
+    assert B.vgg_padded_channels(7, 64) == 0
+
+
+def test_argument_validation_happens_on_the_host():
+    L = B.lib()
+    a = 4096  # a 16-byte aligned fake address; validation must fail before it is ever used
+    assert L.vgg_conv3x3_fwd(0, 1, 4, 4, 16, 16, None, a, None, a, 1, None, 0, None) == -1
+    assert L.vgg_conv3x3_fwd(5, 1, 4, 4, 16, 16, a, a, None, a, 1, None, 0, None) == -3
+    assert L.vgg_conv3x3_fwd(0, 0, 4, 4, 16, 16, a, a, None, a, 1, None, 0, None) == -2
+    assert L.vgg_conv3x3_fwd(0, 1, 4, 4, 16, 16, a + 4, a, None, a, 1, None, 0, None) == -4
+    assert L.vgg_conv3x3_fwd(0, 1, 4, 4, 3, 16, a, a, None, a, 1, None, 0, None) == -5   # needs a padded copy
+    assert L.vgg_conv3x3_bwd_weight(1, 1, 4, 4, 16, 16, a, a, a, None, a, 1 << 30, None) == -7  # bf16 training
+    assert L.vgg_conv3x3_bwd_weight(0, 1, 4, 4, 16, 16, a, a, a, None, None, 0, None) == -5
+    assert L.vgg_maxpool2x2(0, 1, 5, 4, 8, a, a, None, None) == -2                        # odd H
+    assert L.vgg_maxpool2x2(0, 1, 4, 4, 8, None, a, None, None) == -1
+    assert L.vgg_fc(0, 2, 48, 8, a, a, None, a, 0, 0, a, 1 << 30, None) == -2             # In % 32
+    assert L.vgg_fc(0, 2, 64, 8, a, a, None, a, 0, 0, None, 0, None) == -5
+    assert L.vgg_softmax(0, 10, a, a, None) == -2
+    assert L.vgg_sgd_update(0, a, a, 0.1, None) == -2
+    assert L.vgg_sgd_update(4, None, a, 0.1, None) == -1
+
+
+def test_model_level_validation_and_sizes():
+    cfg = B.make_config(B.F32, 2, 32, 32, 512, 10)
+    bad = B.make_config(B.F32, 2, 30, 32, 512, 10)
+    assert B.vgg19_packed_bytes(bad) == 0 and B.vgg19_forward_workspace_bytes(bad) == 0
+    nparams = sum(9 * ci * co + co for ci, co in
+                  [(3, 64), (64, 64), (64, 128), (128, 128), (128, 256)] + [(256, 256)] * 3 + [(256, 512)] +
+                  [(512, 512)] * 7) + 512 * 512 + 512 + 512 * 512 + 512 + 512 * 10 + 10
+    pb = B.vgg19_packed_bytes(cfg)
+    assert nparams * 4 <= pb <= nparams * 4 + 9 * 64 * 13 * 4 + 64 * 256      # padding of conv1_1 + alignment
+    assert B.vgg19_forward_workspace_bytes(cfg) > 2 * 2 * 32 * 32 * 64 * 4
+    assert B.vgg19_train_workspace_bytes(cfg) > B.vgg19_forward_workspace_bytes(cfg)
+    bf = B.make_config(B.BF16, 2, 32, 32, 512, 10)
+    assert B.vgg19_train_workspace_bytes(bf) == 0
+    L = B.lib()
+    a = 4096
+    assert L.vgg19_forward(C.byref(cfg), a, a, a, a, None, 0, None) == -5
+    assert L.vgg19_forward(C.byref(bad), a, a, a, a, a, 1 << 40, None) == -2
+    assert L.vgg19_forward(None, a, a, a, a, a, 1 << 40, None) == -1
+    assert L.vgg19_train_step(C.byref(bf), a, a, a, 1 << 40, None, a, a, a, 1 << 40, None) == -7
+    full = B.make_config(B.F32, 100, 224, 224, 4096, 1000)
+    assert B.vgg19_packed_bytes(full) >= 143667240 * 4
+
+
+def test_launch_plan_matches_paper_op_counts():
+    gold = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "hlo_counts.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, f, b = line.split()
+        gold[name] = (int(f), int(b))
+    cfg = B.make_config(B.F32, 100, 224, 224, 4096, 1000)
+    fwd = B.vgg19_plan(cfg, False)
+    assert fwd.count(1) == gold["convolution"][0] == 16
+    assert fwd.count(4) == gold["reduce-window"][0] == 5
+    assert fwd.count(6) == gold["dot"][0] == 3
+    tr = B.vgg19_plan(cfg, True)
+    # 47 convolutions = 16 forward + 16 weight gradients + 15 data gradients (none for the first layer)
+    assert tr.count(1) + tr.count(2) + tr.count(3) == gold["convolution"][1] == 47
+    assert tr.count(2) == 15 and tr.count(3) == 16
+    assert tr.count(5) == gold["select-and-scatter"][1] == 5
+    assert tr.count(6) + tr.count(7) + tr.count(8) == gold["dot"][1] == 9

@@ -1,0 +1,238 @@
+"""Per-operation parity of the HIP kernels against the fp64 CPU oracle, through
+the C ABI, on seeded inputs at sizes that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vgg_ref as R
+from paper_1810_09868_amd import binding as B
+from paper_1810_09868_amd import synth
+
+from gpu_util import TDT, TOL, dev, from_nhwc, max_rel_err, to_nhwc, ws_bytes
+
+pytestmark = pytest.mark.gpu
+
+# (N, H, W, Cin, Cout): 2-D patch tiling (H, W multiples of 16), linear tiling with images and rows
+# crossing inside a tile, ragged channel counts, a last partial tile, tiny images.
+CONV_SHAPES = [
+    (2, 32, 32, 64, 128),
+    (3, 14, 14, 32, 64),
+    (2, 28, 28, 96, 160),
+    (3, 5, 7, 3, 20),
+    (1, 2, 2, 16, 64),
+    (5, 16, 48, 32, 192),
+    (1, 56, 56, 64, 64),
+]
+
+
+def _pack(dtype, w, flip=0):
+    Cout, Cin = w.shape[:2]
+    rows, cols = (Cin, Cout) if flip else (Cout, Cin)
+    out = torch.empty((9, rows, B.vgg_padded_channels(dtype, cols)), dtype=TDT[dtype], device="cuda")
+    B.vgg_conv_pack_weights(dtype, Cin, Cout, dev(w), out, flip)
+    return out
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv3x3_fwd(dtype, shape):
+    N, H, W, Cin, Cout = shape
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape))
+    ref = R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=True)
+    x = to_nhwc(d["x"], dtype)
+    y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), y, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
+    # no bias, no ReLU
+    ref2 = R.conv3x3_fwd(d["x"], d["w"], None, relu=False)
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), None, y, 0, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y), ref2) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv3x3_bwd_data(dtype, shape):
+    N, H, W, Cin, Cout = shape
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape) + 1)
+    ref = R.conv3x3_bwd_data(d["dy"], d["w"])
+    g = to_nhwc(d["dy"], dtype)
+    dx = torch.empty((N, H, W, Cin), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    wtf = _pack(dtype, d["w"], flip=1)
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, None, dx, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(dx), ref) <= TOL[dtype]
+    # fused ReLU backward of the producer of x: dx * (x > 0)
+    xsrc = to_nhwc(d["x"], dtype)
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, xsrc, dx, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(dx), ref * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv3x3_bwd_weight(shape):
+    N, H, W, Cin, Cout = shape
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape) + 2)
+    dw_ref, db_ref = R.conv3x3_bwd_weight(d["x"], d["dy"])
+    x = to_nhwc(d["x"], B.F32)
+    g = to_nhwc(d["dy"], B.F32)
+    cp = B.vgg_padded_channels(B.F32, Cin)
+    dwp = torch.full((9, Cout, cp), float("nan"), device="cuda")
+    db = torch.empty((Cout,), device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_bwd_weight_workspace_bytes(B.F32, N, H, W, Cin, Cout))
+    B.vgg_conv3x3_bwd_weight(B.F32, N, H, W, Cin, Cout, x, g, dwp, db, ws)
+    dw = torch.empty((Cout, Cin, 3, 3), device="cuda")
+    B.vgg_conv_unpack_weights(Cin, Cout, dwp, dw)
+    torch.cuda.synchronize()
+    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[B.F32]
+    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[B.F32]
+    assert (dwp[:, :, Cin:] == 0).all()     # padding channels get exact zeros
+    # run-to-run reproducibility of the split reduction
+    dwp2 = torch.empty_like(dwp)
+    B.vgg_conv3x3_bwd_weight(B.F32, N, H, W, Cin, Cout, x, g, dwp2, db, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dwp, dwp2)
+
+
+def test_pack_unpack_roundtrip_and_flip_layout():
+    rng = np.random.default_rng(3)
+    Cin, Cout = 5, 12
+    w = rng.standard_normal((Cout, Cin, 3, 3)).astype(np.float32)
+    p = _pack(B.F32, w)
+    back = torch.empty((Cout, Cin, 3, 3), device="cuda")
+    B.vgg_conv_unpack_weights(Cin, Cout, p, back)
+    assert np.array_equal(back.cpu().numpy(), w)
+    pf = _pack(B.F32, w, flip=1).cpu().numpy()       # [9][Cin][CoutP]
+    for t in range(9):
+        assert np.array_equal(pf[t, :, :Cout], w.reshape(Cout, Cin, 9)[:, :, 8 - t].T)
+    assert not pf[:, :, Cout:].any()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", [(2, 8, 12, 64), (3, 2, 2, 8), (1, 14, 14, 512)])
+def test_maxpool_fwd_bwd(dtype, shape):
+    N, H, W, Cc = shape
+    rng = np.random.default_rng(sum(shape))
+    x = rng.standard_normal((N, Cc, H, W)).astype(np.float32)
+    xd = to_nhwc(x, dtype)
+    xq = from_nhwc(xd)                        # what the kernel sees (bf16-rounded for BF16)
+    p_ref, a_ref = R.maxpool2x2(xq)
+    y = torch.empty((N, H // 2, W // 2, Cc), dtype=TDT[dtype], device="cuda")
+    arg = torch.empty((N, H // 2, W // 2, Cc), dtype=torch.uint8, device="cuda")
+    B.vgg_maxpool2x2(dtype, N, H, W, Cc, xd, y, arg)
+    torch.cuda.synchronize()
+    assert np.array_equal(from_nhwc(y), p_ref)                 # selection only: bit-exact
+    a_gpu = arg.permute(0, 3, 1, 2).cpu().numpy()
+    if dtype == B.F32:
+        assert np.array_equal(a_gpu, a_ref)                    # random fp32 data has no ties
+    else:
+        # bf16 rounding creates ties; the oracle consumed the same rounded values, first-max rule applies
+        assert np.array_equal(a_gpu, a_ref)
+    dp = rng.standard_normal(p_ref.shape).astype(np.float32)
+    dpd = to_nhwc(dp, dtype)
+    dx = torch.full((N, H, W, Cc), float("nan"), dtype=TDT[dtype], device="cuda")
+    B.vgg_maxpool2x2_bwd(dtype, N, H, W, Cc, dpd, arg, dx)
+    torch.cuda.synchronize()
+    assert np.array_equal(from_nhwc(dx), R.maxpool2x2_bwd(from_nhwc(dpd), a_ref))
+
+
+def test_maxpool_ties_pick_first():
+    x = np.zeros((1, 8, 4, 4), dtype=np.float32)
+    x[0, 1] = 3.0
+    x[0, 2, 1, 1] = 1.0
+    xd = to_nhwc(x, B.F32)
+    y = torch.empty((1, 2, 2, 8), device="cuda")
+    arg = torch.empty((1, 2, 2, 8), dtype=torch.uint8, device="cuda")
+    B.vgg_maxpool2x2(B.F32, 1, 4, 4, 8, xd, y, arg)
+    _, a_ref = R.maxpool2x2(x)
+    assert np.array_equal(arg.permute(0, 3, 1, 2).cpu().numpy(), a_ref)
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200)])
+def test_fc_forward(dtype, shape):
+    N, In, Out = shape
+    rng = np.random.default_rng(sum(shape))
+    a = rng.standard_normal((N, In)).astype(np.float32)
+    w = (rng.standard_normal((Out, In)) * np.sqrt(2.0 / In)).astype(np.float32)
+    b = rng.standard_normal(Out).astype(np.float32)
+    ws = ws_bytes(B.vgg_fc_workspace_bytes(dtype, N, In, Out))
+    for relu, zdt in ((1, dtype), (0, B.F32)):
+        ref = R.fc(a, w, b, relu=bool(relu))
+        z = torch.empty((N, Out), dtype=TDT[zdt], device="cuda")
+        B.vgg_fc(dtype, N, In, Out, dev(a, TDT[dtype]), dev(w, TDT[dtype]), dev(b), z, zdt, relu, ws)
+        torch.cuda.synchronize()
+        assert max_rel_err(z.float().cpu().numpy(), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200)])
+def test_fc_backward(shape):
+    N, In, Out = shape
+    rng = np.random.default_rng(sum(shape) + 5)
+    a = rng.standard_normal((N, In)).astype(np.float32)
+    w = (rng.standard_normal((Out, In)) * np.sqrt(2.0 / In)).astype(np.float32)
+    dz = rng.standard_normal((N, Out)).astype(np.float32)
+    dw_ref, db_ref, da_ref = R.fc_bwd(a, w, dz)
+    dw = torch.empty((Out, In), device="cuda")
+    db = torch.empty((Out,), device="cuda")
+    da = torch.empty((N, In), device="cuda")
+    ws = ws_bytes(B.vgg_fc_bwd_workspace_bytes(B.F32, N, In, Out))
+    B.vgg_fc_bwd(B.F32, N, In, Out, dev(a), dev(w), dev(dz), dw, db, da, 0, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[B.F32]
+    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[B.F32]
+    assert max_rel_err(da.cpu().numpy(), da_ref) <= TOL[B.F32]
+    B.vgg_fc_bwd(B.F32, N, In, Out, dev(a), dev(w), dev(dz), dw, None, da, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(da.cpu().numpy(), da_ref * (a > 0)) <= TOL[B.F32]
+
+
+@pytest.mark.parametrize("shape", [(100, 1000), (2, 10), (5, 64), (3, 129)])
+def test_softmax_xent_sgd(shape):
+    N, K = shape
+    rng = np.random.default_rng(N * K)
+    z = (rng.standard_normal((N, K)) * 3).astype(np.float32)
+    labels = rng.integers(0, K, size=N).astype(np.int32)
+    p_ref = R.softmax(z)
+    p = torch.empty((N, K), device="cuda")
+    B.vgg_softmax(N, K, dev(z), p)
+    torch.cuda.synchronize()
+    assert max_rel_err(p.cpu().numpy(), p_ref) <= 1e-5
+    loss_ref, dz_ref = R.softmax_xent(p.cpu().numpy().astype(np.float64), labels)
+    loss = torch.empty((1,), device="cuda")
+    dz = torch.empty((N, K), device="cuda")
+    B.vgg_softmax_xent_bwd(N, K, p, dev(labels), loss, dz, ws_bytes(N * 4))
+    torch.cuda.synchronize()
+    assert abs(loss.item() - loss_ref) <= 1e-5 * abs(loss_ref)
+    assert max_rel_err(dz.cpu().numpy(), dz_ref) <= 1e-6
+    n = N * K + 3 if (N * K) % 4 else N * K - 1      # exercise the scalar tail
+    theta = rng.standard_normal(n).astype(np.float32)
+    grad = rng.standard_normal(n).astype(np.float32)
+    th = dev(theta)
+    B.vgg_sgd_update(n, th, dev(grad), 0.01)
+    torch.cuda.synchronize()
+    ref = R.sgd(theta, grad, 0.01)
+    assert np.abs(th.cpu().numpy() - ref).max() <= 1e-6
+
+
+def test_layout_roundtrip_and_convert():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((2, 3, 6, 10)).astype(np.float32)
+    y = torch.empty((2, 6, 10, 16), device="cuda")
+    B.vgg_nchw_to_nhwc(B.F32, 2, 3, 6, 10, 16, dev(x), y)
+    assert np.array_equal(y[..., :3].permute(0, 3, 1, 2).cpu().numpy(), x) and not y[..., 3:].any()
+    back = torch.empty((2, 3, 6, 10), device="cuda")
+    B.vgg_nhwc_to_nchw(B.F32, 2, 3, 6, 10, 16, y, back)
+    assert np.array_equal(back.cpu().numpy(), x)
+    # fp32 -> bf16 is round-to-nearest-even: torch implements the same IEEE rule
+    v = dev(rng.standard_normal(1000).astype(np.float32))
+    out = torch.empty((1000,), dtype=torch.bfloat16, device="cuda")
+    B.vgg_convert(B.F32, B.BF16, 1000, v, out)
+    assert torch.equal(out, v.to(torch.bfloat16))
+    halfway = torch.tensor([1.00390625, 1.01171875], device="cuda")   # exactly between two bf16 values
+    o2 = torch.empty((2,), dtype=torch.bfloat16, device="cuda")
+    B.vgg_convert(B.F32, B.BF16, 2, halfway, o2)
+    assert o2.float().tolist() == [1.0, 1.015625]                     # ties go to the even mantissa
