@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark: VGG19 forward images/s at batch 100, 224x224, on one MI355X.
+
+One step = one whole forward pass (NCHW->NHWC transform, 16 convolutions with
+bias+ReLU, 5 max-pools, 3 dense layers, softmax) over one batch of synthetic
+images that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype bf16|f32]
+
+The roofline figures come from a second pass of the same K steps in which the
+library brackets every launch with HIP events on the launch stream
+(vgg19_timed); doing that inside the main timed loop would perturb `value`.
+The CPU baseline is the fp64 oracle timed on a few images of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+CONV = [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56),
+        (256, 256, 56), (256, 256, 56), (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 28),
+        (512, 512, 14), (512, 512, 14), (512, 512, 14), (512, 512, 14)]
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
+HBM_GBS = 8000.0
+
+
+def conv_flops(N, l):
+    ci, co, hw = CONV[l]
+    return 2.0 * N * hw * hw * 9 * ci * co
+
+
+def run_forward_bench(dtype_name, N, steps, warmup, inp):
+    import torch
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd.model import Vgg19
+    dtype = B.BF16 if dtype_name == "bf16" else B.F32
+    m = Vgg19(dtype, N, 224, 224, 4096, 1000)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    x = torch.from_numpy(inp.x).cuda()
+    for _ in range(warmup):
+        m.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        m.forward(x)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    # per-launch pass (HIP events inside the library, on the launch stream)
+    conv_ms = [0.0] * 16
+    other_ms = {"pool": 0.0, "fc": 0.0, "other": 0.0}
+    for _ in range(steps):
+        kinds, ms = B.vgg19_timed(m.cfg, False, x, None, m.packed, m.logits, m.ws)
+        ci = 0
+        for k, t in zip(kinds, ms):
+            if k == 1:
+                conv_ms[ci] += t / steps
+                ci += 1
+            elif k == 4:
+                other_ms["pool"] += t / steps
+            elif k == 6:
+                other_ms["fc"] += t / steps
+            else:
+                other_ms["other"] += t / steps
+    total_conv_ms = sum(conv_ms)
+    total_conv_flops = sum(conv_flops(N, l) for l in range(16))
+    # dominant kernel: the 128-channel-wide tile instantiation, used by every layer with Cout > 64
+    wide = [l for l in range(16) if CONV[l][1] > 64]
+    wide_flops = sum(conv_flops(N, l) for l in wide) / len(wide)       # algorithmic flops per launch
+    wide_ms = sum(conv_ms[l] for l in wide) / len(wide)                # average launch duration
+    achieved = wide_flops / (wide_ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[dtype_name]
+    res = {
+        "ms_per_step": dt * 1e3,
+        "images_per_s": N / dt,
+        "conv_ms_per_step": total_conv_ms,
+        "conv_tflops": total_conv_flops / (total_conv_ms * 1e-3) / 1e12,
+        "pct_mfma_peak_conv": 100.0 * total_conv_flops / (total_conv_ms * 1e-3) / 1e12 / peak,
+        "other_ms_per_step": other_ms,
+        "per_layer": [{"layer": l, "ms": round(conv_ms[l], 4),
+                       "tflops": round(conv_flops(N, l) / (conv_ms[l] * 1e-3) / 1e12, 1)} for l in range(16)],
+        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_kernel<%s,256,128,2,2>" % ("bf16" if dtype_name == "bf16" else "float"),
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "launches_per_step": len(wide), "avg_launch_ms": wide_ms, "traffic": None},
+    }
+    del m
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(inp, images):
+    from oracle import vgg_ref as R
+    t0 = time.perf_counter()
+    R.vgg19_forward(inp.x[:images], inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    dt = time.perf_counter() - t0
+    return {"value": images / dt, "unit": "images/s", "cores": R.num_threads(), "kind": "oracle",
+            "sample": "fp64 oracle forward pass on the first %d of the 100 images (%.1f s)" % (images, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--batch", type=int, default=100)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true")
+    ap.add_argument("--cpu-images", type=int, default=4)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library is the only implementation", file=sys.stderr)
+        sys.exit(1)
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd import synth
+    B.lib()
+    inp = synth.full_config(a.batch, seed=0, with_labels=False)
+    main_res = run_forward_bench(a.dtype, a.batch, a.steps, a.warmup, inp)
+    out = {
+        "metric": "VGG19 fwd images/s at batch 100, 224x224; conv TFLOP/s and % MFMA peak",
+        "value": main_res["images_per_s"],
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if a.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": ("configs[3]: full VGG19 forward, bf16 weights/activations, fp32 MFMA accumulation, "
+                                if a.dtype == "bf16" else "configs[2]: full VGG19 forward, fp32, ") +
+                               "batch %d, 3x224x224, classifier 25088-4096-4096-1000" % a.batch,
+                   "batch": a.batch, "image": "3x224x224"},
+        "conv_tflops": main_res["conv_tflops"],
+        "conv_ms_per_step": main_res["conv_ms_per_step"],
+        "pct_mfma_peak_conv": main_res["pct_mfma_peak_conv"],
+        "other_ms_per_step": main_res["other_ms_per_step"],
+        "per_layer": main_res["per_layer"],
+        "roofline": main_res["roofline"],
+        "paper_context": {"tpu_v2_core_compute_s_batch100": 0.23, "flux_cpu_s_batch100": 52.4},
+    }
+    if not a.no_secondary:
+        other = "f32" if a.dtype == "bf16" else "bf16"
+        sec = run_forward_bench(other, a.batch, max(3, a.steps // 4), 2, inp)
+        out["secondary"] = {"workload": "configs[2] fp32" if other == "f32" else "configs[3] bf16",
+                            "dtype": other, "images_per_s": sec["images_per_s"], "ms_per_step": sec["ms_per_step"],
+                            "conv_tflops": sec["conv_tflops"], "pct_mfma_peak_conv": sec["pct_mfma_peak_conv"],
+                            "roofline": sec["roofline"]}
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, min(a.cpu_images, a.batch))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -237,6 +237,20 @@ int vgg19_train_step(const vgg_config *cfg, const float *x_nchw, const int32_t *
  * 6 dense fwd, 7 dense bwd (dW), 8 dense bwd (dA), 9 other. */
 int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
 
+/* Profiling variant of the two model-level calls: runs one forward pass
+ * (training == 0) or one training step (training != 0) with a HIP event
+ * recorded on `stream` before every step of the launch plan, WAITS for the
+ * stream to drain, and writes the kind code (as in vgg19_plan) and the
+ * elapsed milliseconds of every step to kinds_host / ms_host (host memory,
+ * `cap` entries each, cap >= the plan length else VGG_ERR_WORKSPACE).
+ * Returns the number of steps or a negative vgg_status.  Unlike every other
+ * entry point it creates and destroys HIP events and synchronises; it exists
+ * for measurement only.  Steps that issue two kernels (a dense layer and its
+ * split reduction) are timed as one. */
+int vgg19_timed(const vgg_config *cfg, int training, const float *x_nchw, const int32_t *labels,
+                void *packed, size_t packed_bytes, float *logits, void *ws, size_t ws_bytes,
+                int *kinds_host, float *ms_host, int cap, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,8 +9,8 @@
  * Every function is the textbook definition written out as direct loops in
  * double precision.  Layouts are the canonical ones: activations
  * [N][C][H][W], convolution weights [Cout][Cin][3][3], dense weights
- * [Out][In], all row-major.  The only parallelism is an OpenMP loop over the
- * batch index (or over output rows where there is no batch index).
+ * [Out][In], all row-major.  The only parallelism is an OpenMP loop over
+ * independent output slices (image and channel, or output rows).
  *
  * What the paper fixes (section "VGG19 forward pass", section "VGG19
  * backward pass", the listing defining dense and softmax, and the appendix
@@ -61,7 +61,7 @@ int ref_conv3x3_fwd(int N, int Cin, int Cout, int H, int W,
     if (!x || !wt || !y) return REF_ERR_NULL;
     if (N <= 0 || Cin <= 0 || Cout <= 0 || H <= 0 || W <= 0) return REF_ERR_SHAPE;
     const size_t HW = (size_t)H * W;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for collapse(2) schedule(dynamic)
     for (int n = 0; n < N; ++n) {
         for (int co = 0; co < Cout; ++co) {
             double *yp = y + ((size_t)n * Cout + co) * HW;
@@ -104,7 +104,7 @@ int ref_conv3x3_bwd_data(int N, int Cin, int Cout, int H, int W,
     if (!g || !wt || !dx) return REF_ERR_NULL;
     if (N <= 0 || Cin <= 0 || Cout <= 0 || H <= 0 || W <= 0) return REF_ERR_SHAPE;
     const size_t HW = (size_t)H * W;
-#pragma omp parallel for schedule(dynamic)
+#pragma omp parallel for collapse(2) schedule(dynamic)
     for (int n = 0; n < N; ++n) {
         for (int ci = 0; ci < Cin; ++ci) {
             double *dp = dx + ((size_t)n * Cin + ci) * HW;

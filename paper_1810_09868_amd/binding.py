@@ -28,6 +28,7 @@ EXPORTS = [
     "vgg_softmax", "vgg_softmax_xent_bwd", "vgg_sgd_update",
     "vgg19_packed_bytes", "vgg19_forward_workspace_bytes", "vgg19_train_workspace_bytes",
     "vgg19_pack_params", "vgg19_unpack_params", "vgg19_forward", "vgg19_train_step", "vgg19_plan",
+    "vgg19_timed",
 ]
 
 
@@ -96,6 +97,8 @@ def lib() -> C.CDLL:
         L.vgg19_forward.argtypes = [cfgp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.vgg19_train_step.argtypes = [cfgp, _vp, _vp, _vp, _sz, prmp, _vp, _vp, _vp, _sz, _vp]
         L.vgg19_plan.argtypes = [cfgp, _i, C.POINTER(C.c_int), _i]
+        L.vgg19_timed.argtypes = [cfgp, _i, _vp, _vp, _vp, _sz, _vp, _vp, _sz, C.POINTER(C.c_int),
+                                  C.POINTER(C.c_float), _i, _vp]
         _LIB = L
     return _LIB
 
@@ -266,3 +269,17 @@ def vgg19_plan(cfg, training: bool) -> List[int]:
     buf = (C.c_int * n)()
     lib().vgg19_plan(C.byref(cfg), int(training), buf, n)
     return list(buf)
+
+
+def vgg19_timed(cfg, training: bool, x_nchw, labels, packed, logits, ws):
+    """Returns (kinds, ms): per-step kind codes and elapsed milliseconds of one pass."""
+    n = lib().vgg19_plan(C.byref(cfg), int(training), None, 0)
+    if n < 0:
+        raise VggError(n, "vgg19_plan")
+    kinds = (C.c_int * n)()
+    ms = (C.c_float * n)()
+    rc = lib().vgg19_timed(C.byref(cfg), int(training), _ptr(x_nchw), _ptr(labels), _ptr(packed), _nbytes(packed),
+                           _ptr(logits), _ptr(ws), _nbytes(ws), kinds, ms, n, _stream())
+    if rc < 0:
+        raise VggError(rc, "vgg19_timed")
+    return list(kinds), list(ms)

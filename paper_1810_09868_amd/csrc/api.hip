@@ -167,10 +167,13 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
 // Records the launch plan and, unless dry, stops at the first failing launch.
 struct Recorder {
     int *kinds; int cap; int n; bool dry; int rc;
+    hipEvent_t *events = nullptr;  // when set (cap+1 events): one is recorded before every step
+    hipStream_t stream = nullptr;
     bool skip(int kind)
     {
         if (rc != VGG_OK) return true;
         if (kinds && n < cap) kinds[n] = kind;
+        if (events && !dry && n < cap && hipEventRecord(events[n], stream) != hipSuccess) rc = VGG_ERR_LAUNCH;
         ++n;
         return dry;
     }
@@ -623,6 +626,48 @@ int vgg19_train_step(const vgg_config *cfg, const float *x, const int32_t *label
     run_train(cfg, P, L, x, labels, static_cast<char *>(packed), grads, loss, logits, static_cast<char *>(ws),
               (hipStream_t)stream, rec);
     return rec.rc;
+}
+
+int vgg19_timed(const vgg_config *cfg, int training, const float *x, const int32_t *labels, void *packed,
+                size_t packed_bytes, float *logits, void *ws, size_t ws_bytes, int *kinds_host, float *ms_host, int cap,
+                void *stream)
+{
+    if (!cfg || !x || !packed || !kinds_host || !ms_host || (training && !labels)) return VGG_ERR_NULL;
+    if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
+    if (training && cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (!cfg_ok(cfg) || cap <= 0) return VGG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(packed) || (logits && !aligned16(logits)) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
+    const PackedLayout P = packed_layout(cfg);
+    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    const WsLayout L = ws_layout(cfg, P, training != 0);
+    if (!ws || ws_bytes < L.total) return VGG_ERR_WORKSPACE;
+    const int need = vgg19_plan(cfg, training, nullptr, 0);
+    if (need < 0) return need;
+    if (cap < need) return VGG_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t *ev = new hipEvent_t[need + 1];
+    int made = 0;
+    int rc = VGG_OK;
+    for (; made <= need; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) { rc = VGG_ERR_LAUNCH; break; }
+    if (rc == VGG_OK) {
+        Recorder rec{kinds_host, need, 0, false, VGG_OK};
+        rec.events = ev;
+        rec.stream = s;
+        if (training)
+            run_train(cfg, P, L, x, labels, static_cast<char *>(packed), nullptr, nullptr, logits, static_cast<char *>(ws), s, rec);
+        else
+            run_forward(cfg, P, L, x, static_cast<const char *>(packed), logits, nullptr, true, static_cast<char *>(ws), false, s, rec);
+        rc = rec.rc;
+        if (rc == VGG_OK && (hipEventRecord(ev[need], s) != hipSuccess || hipEventSynchronize(ev[need]) != hipSuccess))
+            rc = VGG_ERR_LAUNCH;
+        for (int i = 0; i < need && rc == VGG_OK; ++i)
+            if (hipEventElapsedTime(&ms_host[i], ev[i], ev[i + 1]) != hipSuccess) rc = VGG_ERR_LAUNCH;
+        if (rc == VGG_OK) rc = need;
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    delete[] ev;
+    return rc;
 }
 
 int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap)

@@ -186,14 +186,14 @@ int fc_forward(int dtype, int N, int In, int Out, const void *a_, const void *w,
 
 // ------------------------------------------------- backward: dW = dz^T * a
 // fp32.  Workgroup: 128 (o) x 128 (i) block of dW; the batch is the
-// contraction index, staged through LDS 64 rows at a time.  Wave (wo, wi)
+// contraction index, staged through LDS 32 rows at a time.  Wave (wo, wi)
 // owns a 64x64 sub-block = 2x2 MFMA tiles.
 __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a, const float *__restrict__ dz,
                                                     float *__restrict__ dw, int N, int In, int Out)
 {
     constexpr int ROW = 128 * 4 + 16;
-    __shared__ __align__(16) char Ds[64 * ROW];
-    __shared__ __align__(16) char As[64 * ROW];
+    __shared__ __align__(16) char Ds[32 * ROW];
+    __shared__ __align__(16) char As[32 * ROW];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = lane & 31, kp = lane >> 5;
     const int wo = wv & 1, wi = wv >> 1;
@@ -208,9 +208,9 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[x][y][e] = 0.f;
 
-    for (int n0 = 0; n0 < N; n0 += 64) {
+    for (int n0 = 0; n0 < N; n0 += 32) {
         __syncthreads();
-        for (int idx = tid; idx < 64 * 32; idx += 256) {
+        for (int idx = tid; idx < 32 * 32; idx += 256) {
             const int seg = idx & 31, row = idx >> 5;
             uint4 vd = make_uint4(0, 0, 0, 0), va = make_uint4(0, 0, 0, 0);
             if (n0 + row < N) {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
         }
         __syncthreads();
 #pragma unroll 4
-        for (int s = 0; s < 32; ++s) {
+        for (int s = 0; s < 16; ++s) {
             const int n = 2 * s + kp;
             float af[2], bf[2];
 #pragma unroll

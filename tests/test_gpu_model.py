@@ -1,0 +1,158 @@
+"""Whole-model parity of the HIP path against the fp64 CPU oracle: the tiny
+VGG19 (forward in both dtypes, training step), the single-layer
+microbenchmark shape, and the full 224x224 batch-100 configurations on sampled
+images / via batch linearity."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vgg_ref as R
+from paper_1810_09868_amd import binding as B
+from paper_1810_09868_amd import synth
+from paper_1810_09868_amd.model import Vgg19
+
+from gpu_util import TDT, TOL, dev, from_nhwc, max_rel_err, to_nhwc, ws_bytes
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(lst):
+    return [a.astype(np.float64) for a in lst]
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_tiny_vgg19_forward(dtype):
+    inp = synth.tiny_config(seed=0)
+    ref = R.vgg19_forward(inp.x, inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    m = Vgg19(dtype, 2, 32, 32, 512, 10)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    m.forward(dev(inp.x))
+    torch.cuda.synchronize()
+    assert max_rel_err(m.logits.cpu().numpy(), ref["logits"]) <= TOL[dtype]
+    assert max_rel_err(m.probs.cpu().numpy(), ref["probs"]) <= TOL[dtype]
+    np.testing.assert_allclose(m.probs.sum(1).cpu().numpy(), 1.0, atol=1e-5)
+
+
+def test_tiny_vgg19_train_step_fp32():
+    inp = synth.tiny_config(seed=0)
+    ref = R.vgg19_train_step(inp.x, inp.labels, _f64(inp.conv_w), _f64(inp.conv_b), _f64(inp.fc_w),
+                             _f64(inp.fc_b), lr=0.01)
+    m = Vgg19(B.F32, 2, 32, 32, 512, 10, lr=0.01, training=True)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    before = m.unpack()
+    for k, src in (("conv_w", inp.conv_w), ("conv_b", inp.conv_b), ("fc_w", inp.fc_w), ("fc_b", inp.fc_b)):
+        for a, b in zip(before[k], src):
+            assert np.array_equal(a, b)                    # pack -> unpack is the identity
+    g = m.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
+    torch.cuda.synchronize()
+    tol = TOL[B.F32]
+    assert abs(m.loss.item() - ref["loss"]) <= tol * abs(ref["loss"])
+    assert max_rel_err(m.logits.cpu().numpy(), ref["logits"]) <= tol
+    worst = 0.0
+    for k, rk in (("conv_w", "dconv_w"), ("conv_b", "dconv_b"), ("fc_w", "dfc_w"), ("fc_b", "dfc_b")):
+        for l, (a, b) in enumerate(zip(g[k], ref[rk])):
+            e = max_rel_err(a.cpu().numpy(), b)
+            worst = max(worst, e)
+            assert e <= tol, (k, l, e)
+    after = m.unpack()
+    for k, rk in (("conv_w", "new_conv_w"), ("conv_b", "new_conv_b"), ("fc_w", "new_fc_w"), ("fc_b", "new_fc_b")):
+        for l, (a, b) in enumerate(zip(after[k], ref[rk])):
+            assert max_rel_err(a, b) <= tol, (k, l)
+            # the update itself (theta - lr*grad), not just theta, must match
+            upd = a.astype(np.float64) - before[k][l].astype(np.float64)
+            refupd = b - before[k][l].astype(np.float64)
+            assert np.abs(upd - refupd).max() <= tol * np.abs(refupd).max() + 1e-9, (k, l)
+    print("worst gradient error", worst)
+
+
+def test_conv_microbenchmark_shape_sampled_images():
+    # 128 -> 256 channels, 56x56, batch 100 on the GPU; the oracle recomputes three of the images
+    N, H, W, Cin, Cout = 100, 56, 56, 128, 256
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=0)
+    for dtype in (B.F32, B.BF16):
+        x = to_nhwc(d["x"], dtype)
+        wp = torch.empty((9, Cout, Cin), dtype=TDT[dtype], device="cuda")
+        B.vgg_conv_pack_weights(dtype, Cin, Cout, dev(d["w"]), wp, 0)
+        y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+        B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, wp, dev(d["b"]), y, 1, None)
+        torch.cuda.synchronize()
+        for n in (0, 57, 99):
+            ref = R.conv3x3_fwd(d["x"][n:n + 1], d["w"], d["b"], relu=True)
+            assert max_rel_err(from_nhwc(y[n:n + 1]), ref) <= TOL[dtype], (dtype, n)
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_full_vgg19_forward_batch100_sampled_images(dtype):
+    N = 100
+    inp = synth.full_config(N, seed=0, with_labels=False)
+    m = Vgg19(dtype, N, 224, 224, 4096, 1000)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    m.forward(dev(inp.x))
+    torch.cuda.synchronize()
+    logits = m.logits.cpu().numpy()
+    probs = m.probs.cpu().numpy()
+    assert np.isfinite(logits).all()
+    np.testing.assert_allclose(probs.sum(1), 1.0, atol=1e-4)
+    for n in (0, 99):
+        ref = R.vgg19_forward(inp.x[n:n + 1], inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+        assert max_rel_err(logits[n:n + 1], ref["logits"]) <= TOL[dtype], n
+        assert max_rel_err(probs[n:n + 1], ref["probs"]) <= TOL[dtype], n
+
+
+def test_full_vgg19_train_step_224_vs_oracle_batch2():
+    inp = synth.vgg19_inputs(2, 224, 224, 4096, 1000, seed=1)
+    ref = R.vgg19_train_step(inp.x, inp.labels, _f64(inp.conv_w), _f64(inp.conv_b), _f64(inp.fc_w),
+                             _f64(inp.fc_b), lr=0.01)
+    m = Vgg19(B.F32, 2, 224, 224, 4096, 1000, lr=0.01, training=True)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    g = m.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
+    torch.cuda.synchronize()
+    tol = TOL[B.F32]
+    assert abs(m.loss.item() - ref["loss"]) <= tol * abs(ref["loss"])
+    assert max_rel_err(m.logits.cpu().numpy(), ref["logits"]) <= tol
+    for k, rk in (("conv_w", "dconv_w"), ("conv_b", "dconv_b"), ("fc_w", "dfc_w"), ("fc_b", "dfc_b")):
+        for l, (a, b) in enumerate(zip(g[k], ref[rk])):
+            assert max_rel_err(a.cpu().numpy(), b) <= tol, (k, l)
+    after = m.unpack()
+    for k, rk in (("conv_w", "new_conv_w"), ("fc_w", "new_fc_w"), ("fc_b", "new_fc_b")):
+        for l, (a, b) in enumerate(zip(after[k], ref[rk])):
+            assert max_rel_err(a, b) <= tol, (k, l)
+
+
+def test_full_vgg19_train_step_batch100_is_mean_of_chunks():
+    # The loss is a mean over images, so the batch-100 gradient equals the mean of the gradients of
+    # five batch-20 steps from the same parameters (a property that holds at any size); the batch-2
+    # test above ties the same kernels at the same spatial sizes to the oracle.
+    N, chunk = 100, 20
+    inp = synth.full_config(N, seed=2)
+    big = Vgg19(B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
+    big.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    gb = big.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
+    torch.cuda.synchronize()
+    loss_big = big.loss.item()
+    logits_big = big.logits.cpu().numpy()
+    gb = {k: [a.double().cpu() for a in v] for k, v in gb.items()}
+    new_big = big.unpack()
+    del big
+    torch.cuda.empty_cache()
+    small = Vgg19(B.F32, chunk, 224, 224, 4096, 1000, lr=0.01, training=True)
+    acc = None
+    losses = []
+    for c in range(N // chunk):
+        sl = slice(c * chunk, (c + 1) * chunk)
+        small.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+        g = small.train_step(dev(inp.x[sl]), dev(inp.labels[sl]), want_grads=True)
+        torch.cuda.synchronize()
+        losses.append(small.loss.item())
+        assert max_rel_err(small.logits.cpu().numpy(), logits_big[sl]) <= 1e-5
+        g = {k: [a.double().cpu() for a in v] for k, v in g.items()}
+        acc = g if acc is None else {k: [a + b for a, b in zip(acc[k], g[k])] for k in acc}
+    assert abs(np.mean(losses) - loss_big) <= 1e-5 * abs(loss_big)
+    for k in acc:
+        for l, (a, b) in enumerate(zip(acc[k], gb[k])):
+            assert max_rel_err(b.numpy(), (a / (N // chunk)).numpy()) <= TOL[B.F32], (k, l)
+    # SGD applied: theta_new = theta - lr * grad
+    for k, src in (("conv_w", inp.conv_w), ("fc_b", inp.fc_b)):
+        for l in range(len(src)):
+            upd = new_big[k][l].astype(np.float64) - src[l].astype(np.float64)
+            assert max_rel_err(upd, -0.01 * gb[k][l].numpy()) <= 1e-3, (k, l)
