@@ -194,6 +194,7 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
     assert len(conv_w) == 16 and len(fc_w) == 3
     out: Dict[str, object] = {}
     acts: List[np.ndarray] = []      # input of every conv layer
+    pres: List[np.ndarray] = []      # pre-activation (bias added, before ReLU) of every conv layer
     ys: List[np.ndarray] = []        # post-ReLU output of every conv layer
     args: Dict[int, np.ndarray] = {}
     h = _f64(x)
@@ -201,57 +202,122 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
         assert conv_w[l].shape == (cout, cin, 3, 3)
         if keep:
             acts.append(h)
-        h = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=True)
-        if keep:
+            pre = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=False)
+            pres.append(pre)
+            h = np.maximum(pre, 0.0)
             ys.append(h)
+        else:
+            h = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=True)
         if l in _POOL_AFTER:
             h, a = maxpool2x2(h)
             if keep:
                 args[l] = a
     N = h.shape[0]
     flat = h.reshape(N, -1)
-    z1 = fc(flat, fc_w[0], fc_b[0], relu=True)
-    z2 = fc(z1, fc_w[1], fc_b[1], relu=True)
+    pre1 = fc(flat, fc_w[0], fc_b[0], relu=False)
+    z1 = np.maximum(pre1, 0.0)
+    pre2 = fc(z1, fc_w[1], fc_b[1], relu=False)
+    z2 = np.maximum(pre2, 0.0)
     logits = fc(z2, fc_w[2], fc_b[2], relu=False)
     out["logits"] = logits
     out["probs"] = softmax(logits)
     if keep:
-        out.update(conv_in=acts, conv_out=ys, pool_arg=args, pool5=h, flat=flat, z1=z1, z2=z2)
+        out.update(conv_in=acts, conv_pre=pres, conv_out=ys, pool_arg=args, pool5=h, flat=flat, z1=z1, z2=z2,
+                   fc_pre=[pre1, pre2])
     return out
 
 
-def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01) -> Dict[str, object]:
-    """One step: forward, mean softmax cross-entropy, full backward, plain SGD.
+def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: float = 0.0,
+                    pool_second_within: float = 0.0) -> Dict[str, object]:
+    """Backward sweep from a kept forward pass ``f`` (vgg19_forward(keep=True)).
 
-    Returns loss, logits, probs, the 38 gradient tensors (dconv_w/dconv_b/
-    dfc_w/dfc_b) and the updated parameters (new_*).  ReLU passes gradient
-    where its output is strictly positive; a pool routes its gradient to the
-    recorded first maximum; the first convolution's input gradient is not
-    formed (the paper's optimised backward pass has 47 convolutions, not 48).
+    With the defaults this is the gradient of the mean softmax cross-entropy:
+    ReLU passes gradient where its output is strictly positive, a pool routes
+    its gradient to the recorded first maximum, and the first convolution's
+    input gradient is not formed (the paper's optimised backward pass has 47
+    convolutions, not 48).
+
+    The two optional arguments produce the neighbours of that gradient which
+    a lower-precision evaluation of the same forward pass may legitimately
+    return, because a ReLU or a window maximum is a discrete decision taken on
+    a floating-point value: with ``mask_shift`` t != 0 every ReLU passes
+    gradient where its pre-activation exceeds t * max|pre-activation| of its
+    layer instead of 0 (t may be negative); with ``pool_second_within`` r > 0
+    every pooling window whose two largest values differ by less than
+    r * max(y) routes its gradient to the second of them instead of the first.
     """
-    f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True)
+    def relu_mask(pre, d):
+        if mask_shift == 0.0:
+            return np.where(pre > 0.0, d, 0.0)
+        return np.where(pre > mask_shift * np.abs(pre).max(), d, 0.0)
+
     loss, dlogits = softmax_xent(f["probs"], labels)
     dfc_w = [None] * 3
     dfc_b = [None] * 3
     dfc_w[2], dfc_b[2], dz2 = fc_bwd(f["z2"], fc_w[2], dlogits)
-    dz2 = relu_bwd(f["z2"], dz2)
+    dz2 = relu_mask(f["fc_pre"][1], dz2)
     dfc_w[1], dfc_b[1], dz1 = fc_bwd(f["z1"], fc_w[1], dz2)
-    dz1 = relu_bwd(f["z1"], dz1)
+    dz1 = relu_mask(f["fc_pre"][0], dz1)
     dfc_w[0], dfc_b[0], dflat = fc_bwd(f["flat"], fc_w[0], dz1)
     d = dflat.reshape(f["pool5"].shape)
     dconv_w = [None] * 16
     dconv_b = [None] * 16
     for l in range(15, -1, -1):
         if l in _POOL_AFTER:
-            d = maxpool2x2_bwd(d, f["pool_arg"][l])
-        g = relu_bwd(f["conv_out"][l], d)
+            arg = f["pool_arg"][l]
+            if pool_second_within > 0.0:
+                arg = _second_best_where_close(f["conv_out"][l], arg, pool_second_within)
+            d = maxpool2x2_bwd(d, arg)
+        g = relu_mask(f["conv_pre"][l], d)
         dconv_w[l], dconv_b[l] = conv3x3_bwd_weight(f["conv_in"][l], g)
         if l > 0:
             d = conv3x3_bwd_data(g, conv_w[l])
-    res = dict(loss=loss, logits=f["logits"], probs=f["probs"],
-               dconv_w=dconv_w, dconv_b=dconv_b, dfc_w=dfc_w, dfc_b=dfc_b)
-    res["new_conv_w"] = [sgd(conv_w[l], dconv_w[l], lr) for l in range(16)]
-    res["new_conv_b"] = [sgd(conv_b[l], dconv_b[l], lr) for l in range(16)]
-    res["new_fc_w"] = [sgd(fc_w[l], dfc_w[l], lr) for l in range(3)]
-    res["new_fc_b"] = [sgd(fc_b[l], dfc_b[l], lr) for l in range(3)]
+    return dict(loss=loss, dconv_w=dconv_w, dconv_b=dconv_b, dfc_w=dfc_w, dfc_b=dfc_b)
+
+
+def _windows(y):
+    N, Cc, H, W = y.shape
+    return y.reshape(N, Cc, H // 2, 2, W // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, Cc, H // 2, W // 2, 4)
+
+
+def _second_best_where_close(y, arg, rel):
+    win = _windows(y)
+    order = np.argsort(-win, axis=-1, kind="stable")
+    top = np.take_along_axis(win, order[..., :2], axis=-1)
+    close = (top[..., 0] - top[..., 1] < rel * np.abs(y).max()) & (top[..., 0] > 0)
+    out = arg.copy()
+    out[close] = order[..., 1][close].astype(np.uint8)
+    return out
+
+
+def decision_margins(f: Dict[str, object]) -> Dict[str, float]:
+    """How far the forward pass ``f`` (keep=True) is from a different discrete
+    decision: the smallest |pre-activation| of any ReLU and the smallest gap
+    between the two largest values of any pooling window with a positive
+    maximum, each relative to the largest magnitude in its layer."""
+    relu = min(float(np.abs(p).min() / np.abs(p).max()) for p in list(f["conv_pre"]) + list(f["fc_pre"]))
+    pool = 1.0
+    for l in _POOL_AFTER:
+        y = f["conv_out"][l]
+        win = np.sort(_windows(y), axis=-1)
+        gap = (win[..., 3] - win[..., 2])[win[..., 3] > 0]
+        if gap.size:
+            pool = min(pool, float(gap.min() / np.abs(y).max()))
+    return {"relu": relu, "pool": pool}
+
+
+def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01) -> Dict[str, object]:
+    """One step: forward, mean softmax cross-entropy, full backward, plain SGD.
+
+    Returns loss, logits, probs, the 38 gradient tensors (dconv_w/dconv_b/
+    dfc_w/dfc_b), the updated parameters (new_*) and the kept forward pass
+    (``fwd``) for vgg19_gradients / decision_margins.
+    """
+    f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True)
+    res = vgg19_gradients(f, labels, conv_w, fc_w)
+    res.update(logits=f["logits"], probs=f["probs"], fwd=f)
+    res["new_conv_w"] = [sgd(conv_w[l], res["dconv_w"][l], lr) for l in range(16)]
+    res["new_conv_b"] = [sgd(conv_b[l], res["dconv_b"][l], lr) for l in range(16)]
+    res["new_fc_w"] = [sgd(fc_w[l], res["dfc_w"][l], lr) for l in range(3)]
+    res["new_fc_b"] = [sgd(fc_b[l], res["dfc_b"][l], lr) for l in range(3)]
     return res
