@@ -89,12 +89,14 @@ struct TileGeom {
     int N, H, W, M;      // M = N*H*W
     int mode;            // 0 LINEAR, 1 TILE2D
     int rows;            // tile rows (pixels)
-    int TH, TW;          // TILE2D patch size (TW a power of two)
+    int TH, TW;          // TILE2D patch size (TW == kTileW)
     int tiles_w, tiles_hw;  // TILE2D: patches per image row / per image
     int ntiles;
     int pitch;
     int S;               // halo rows (upper bound over all tiles)
 };
+
+constexpr int kTileW = 16;  // width of a TILE2D patch (compile-time so that row/column splits are shifts)
 
 struct TileOrigin {
     int n, h0, w0;  // TILE2D
@@ -109,7 +111,7 @@ __device__ __forceinline__ TileOrigin tile_origin(const TileGeom &g, int tile)
         const int rem = tile - o.n * g.tiles_hw;
         const int ty = rem / g.tiles_w;
         o.h0 = ty * g.TH;
-        o.w0 = (rem - ty * g.tiles_w) * g.TW;
+        o.w0 = (rem - ty * g.tiles_w) * kTileW;
         o.m0 = 0; o.q0 = 0;
     } else {
         o.m0 = tile * g.rows;
@@ -124,7 +126,7 @@ __device__ __forceinline__ TileOrigin tile_origin(const TileGeom &g, int tile)
 __device__ __forceinline__ int halo_pixel(const TileGeom &g, const TileOrigin &o, int i)
 {
     if (g.mode) {
-        const int hy = i / (g.TW + 2), hx = i - hy * (g.TW + 2);
+        const int hy = i / (kTileW + 2), hx = i - hy * (kTileW + 2);
         const int h = o.h0 - 1 + hy, w = o.w0 - 1 + hx;
         if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
         return (o.n * g.H + h) * g.W + w;
@@ -140,10 +142,10 @@ __device__ __forceinline__ int halo_pixel(const TileGeom &g, const TileOrigin &o
 __device__ __forceinline__ void tile_row(const TileGeom &g, const TileOrigin &o, int j, int &m, int &hrow)
 {
     if (g.mode) {
-        const int dy = j / g.TW, dx = j - dy * g.TW;
+        const int dy = j / kTileW, dx = j - dy * kTileW;
         const int h = o.h0 + dy, w = o.w0 + dx;
         m = (h < g.H && w < g.W) ? (o.n * g.H + h) * g.W + w : -1;
-        hrow = dy * (g.TW + 2) + dx;
+        hrow = dy * (kTileW + 2) + dx;
         return;
     }
     m = o.m0 + j;
@@ -153,13 +155,24 @@ __device__ __forceinline__ void tile_row(const TileGeom &g, const TileOrigin &o,
     hrow = (n * (g.H + 1) + h) * (g.W + 1) + w - o.q0;
 }
 
+// Output pixel of tile row j only (no halo row: no divisions).
+__device__ __forceinline__ int tile_pixel(const TileGeom &g, const TileOrigin &o, int j)
+{
+    if (g.mode) {
+        const int h = o.h0 + j / kTileW, w = o.w0 + j % kTileW;
+        return (h < g.H && w < g.W) ? (o.n * g.H + h) * g.W + w : -1;
+    }
+    const int m = o.m0 + j;
+    return m < g.M ? m : -1;
+}
+
 // Host side: chooses the mode and fills the derived fields for tiles of
 // `rows` pixels (rows = 256 -> 16x16 patches, 128 -> 8x16).
 inline TileGeom make_tile_geom(int N, int H, int W, int rows)
 {
     TileGeom g;
     g.N = N; g.H = H; g.W = W; g.M = N * H * W; g.rows = rows;
-    g.TW = 16; g.TH = rows / 16;
+    g.TW = kTileW; g.TH = rows / kTileW;
     if (H % g.TH == 0 && W % g.TW == 0) {
         g.mode = 1;
         g.tiles_w = W / g.TW;

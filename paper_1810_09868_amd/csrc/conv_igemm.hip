@@ -19,12 +19,16 @@
 // operand of one v_mfma_f32_32x32x16_bf16; for fp32 the four elements feed
 // four v_mfma_f32_32x32x2_f32 (any fixed pairing of k indices between A and B
 // is a valid contraction order).
+#include <cstdlib>
+
 #include "common.h"
 
 namespace vgg {
 
 constexpr int kRowBytes = 80;  // 64 data + 16 pad
 constexpr int kDataBytes = 64;
+constexpr int kEpiRow = 144;              // epilogue transpose: 128 data bytes + 16 pad per row
+constexpr int kEpiBytes = 32 * kEpiRow;   // per wave
 constexpr int kMaxAHaloSegsPerBlock = 1536;  // 16-byte halo segments (384 rows) prefetched through registers
 
 struct ConvArgs {
@@ -61,8 +65,8 @@ template <> struct Mma<bf16_t> {
     }
 };
 
-template <typename T, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_igemm_kernel(ConvArgs p)
+template <typename T, int BM, int BN, int WM, int WN, int NBUF>
+__global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : 2) void conv3x3_igemm_kernel(ConvArgs p)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;  // 32x32 MFMA tiles per wave along pixels
@@ -73,8 +77,10 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
     const int S = p.g.S;
     const int SA = p.rowsA;                     // rows reserved for the halo (>= S)
     int *pix = reinterpret_cast<int *>(smem);   // [SA] halo row -> input pixel or -1
-    char *As = smem + round_up16(SA * 4);       // [SA][80]
-    char *Bs = As + (size_t)SA * kRowBytes;     // [3][BN][80]
+    char *As = smem + round_up16(SA * 4);              // [NBUF][SA][80]
+    char *Bs = As + (size_t)NBUF * SA * kRowBytes;     // [NBUF][3][BN][80]
+    const int a_bytes = SA * kRowBytes;
+    constexpr int b_bytes = 3 * BN * kRowBytes;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -129,14 +135,14 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
             areg[j] = *reinterpret_cast<const u32x4 *>(src + (idx & 3) * 16);
         }
     };
-    auto store_a = [&](const u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
+    auto store_a = [&](const u32x4(&areg)[MAXA], char *As) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < MAXA; ++j) {
             const int idx = tid + j * NT;
             *reinterpret_cast<u32x4 *>(As + (idx >> 2) * kRowBytes + (idx & 3) * 16) = areg[j];
         }
     };
-    auto copy_a_direct = [&](int c0) __attribute__((always_inline)) {  // halo too large for the register path
+    auto copy_a_direct = [&](int c0, char *As) __attribute__((always_inline)) {  // halo too large for the register path
         for (int idx = tid; idx < nA; idx += NT) {
             const int off = pix[idx >> 2];
             u32x4 v = {0u, 0u, 0u, 0u};
@@ -156,7 +162,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
                 p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + (idx & 3) * 16);
         }
     };
-    auto store_b = [&](const u32x4(&breg)[NB]) __attribute__((always_inline)) {
+    auto store_b = [&](const u32x4(&breg)[NB], char *Bs) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int idx = tid + j * NT;
@@ -166,12 +172,12 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
 
     u32x4 areg[MAXA], breg[NB];
     __syncthreads();  // halo table ready
-    if (a_regs) { load_a(0, areg); store_a(areg); } else copy_a_direct(0);
+    if (a_regs) { load_a(0, areg); store_a(areg, As); } else copy_a_direct(0, As);
     load_b(0, 0, breg);
-    store_b(breg);
+    store_b(breg, Bs);
     __syncthreads();
 
-    auto compute = [&](int kh) __attribute__((always_inline)) {
+    auto compute = [&](int kh, const char *As, const char *Bs) __attribute__((always_inline)) {
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
             const int toff = (kh * pitch + kw) * kRowBytes;
@@ -193,35 +199,88 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
     };
 
     // Software pipeline: the global loads of stage s+1 are issued before the MFMAs of stage s and
-    // land in LDS after them, so their latency is covered by the arithmetic.
-    int kh = 0, c0 = 0;
+    // land in LDS after them, so their latency is covered by the arithmetic.  With NBUF == 2 they
+    // land in the other LDS buffer and one barrier per stage is enough.
+    int kh = 0, c0 = 0, ab = 0, bb = 0;
     for (int s = 0; s + 1 < nstages; ++s) {
         int nkh = kh + 1, nc0 = c0;
         if (nkh == 3) { nkh = 0; nc0 += KC; }
         const bool new_chunk = nkh == 0;
         load_b(nc0, nkh, breg);
         if (new_chunk && a_regs) load_a(nc0, areg);
-        compute(kh);
-        __syncthreads();  // every wave is done reading this stage's LDS data
-        store_b(breg);
+        compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
+        if (NBUF == 1) __syncthreads();  // every wave is done reading this stage's LDS data
+        const int nab = NBUF == 2 && new_chunk ? ab ^ 1 : ab, nbb = NBUF == 2 ? bb ^ 1 : bb;
+        store_b(breg, Bs + nbb * b_bytes);
         if (new_chunk) {
-            if (a_regs) store_a(areg); else copy_a_direct(nc0);
+            if (a_regs) store_a(areg, As + nab * a_bytes); else copy_a_direct(nc0, As + nab * a_bytes);
         }
         __syncthreads();
-        kh = nkh; c0 = nc0;
+        kh = nkh; c0 = nc0; ab = nab; bb = nbb;
     }
-    compute(kh);
+    compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
 
-    // epilogue: bias, ReLU, optional (mask > 0) factor, convert, store.
-    // 32x32 accumulator layout: register e of lane l holds row 8*(e/4) + 4*(l/32) + e%4, column l%32.
+    // Epilogue: bias, ReLU, optional (mask > 0) factor, convert, store.
+    // 32x32 accumulator layout: register e of lane l holds row 8*(e/4) + 4*(l/32) + e%4, column l%32,
+    // i.e. a lane owns single elements of many rows.  Each wave transposes 32 rows x 128 bytes at a
+    // time through a private LDS block so that every lane stores 16 contiguous bytes of one pixel.
     T *y = reinterpret_cast<T *>(p.y);
     const T *mask = reinterpret_cast<const T *>(p.mask);
+    constexpr int VEC = 16 / (int)sizeof(T);        // elements per 16-byte store
+    constexpr int CPT = 128 / (int)sizeof(T);       // columns per transposed pass (64 bf16 / 32 fp32)
+    constexpr int TJ = CPT / 32;                    // MFMA column tiles per pass
+    static_assert(TN % TJ == 0, "wave tile must hold whole passes");
+    __syncthreads();  // staging data no longer needed: LDS is reused
+    if (p.Cout % VEC == 0) {
+        char *epi = smem + wv * kEpiBytes;
+        const int seg = lane & 7, rowq = lane >> 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j0 = 0; j0 < TN; j0 += TJ) {
+#pragma unroll
+                for (int jj = 0; jj < TJ; ++jj) {
+                    const int col = n0 + wn * (BN / WN) + (j0 + jj) * 32 + r;
+                    const float bv = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        float v = acc[i][j0 + jj][e] + bv;
+                        if (p.relu) v = fmaxf(v, 0.f);
+                        const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
+                        Elem<T>::store(reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r, v);
+                    }
+                }
+                const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = rowq + 8 * q;
+                    u32x4 v = *reinterpret_cast<const u32x4 *>(epi + row * kEpiRow + seg * 16);
+                    const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + row);
+                    if (m >= 0 && colbase < p.Cout) {
+                        const size_t o = (size_t)m * p.Cout + colbase;
+                        if (mask) {
+                            const u32x4 mk = *reinterpret_cast<const u32x4 *>(mask + o);
+                            T ve[VEC], me[VEC];
+                            __builtin_memcpy(ve, &v, 16);
+                            __builtin_memcpy(me, &mk, 16);
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k)
+                                if (!(Elem<T>::load(me + k) > 0.f)) ve[k] = (T)0;
+                            __builtin_memcpy(&v, ve, 16);
+                        }
+                        *reinterpret_cast<u32x4 *>(y + o) = v;
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // channel counts that do not allow 16-byte stores: element-wise
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            int m, hrow;
-            tile_row(p.g, org, wm * (BM / WM) + i * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3), m, hrow);
+            const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3));
             if (m < 0) continue;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
@@ -238,7 +297,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM * WN == 8 ? 2 : 2) void conv3x3_ige
     }
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
+template <typename T, int BM, int BN, int WM, int WN, int NBUF>
 static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stream)
 {
     ConvArgs a = a0;
@@ -246,9 +305,10 @@ static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stre
     a.tiles_n = (a.Cout + BN - 1) / BN;
     constexpr int NT = WM * WN * 64;
     a.rowsA = a.g.S * 4 <= kMaxAHaloSegsPerBlock ? kMaxAHaloSegsPerBlock / 4 : a.g.S;
-    const size_t lds = round_up((size_t)a.rowsA * 4, 16) + (size_t)a.rowsA * kRowBytes + (size_t)3 * BN * kRowBytes;
+    size_t lds = round_up((size_t)a.rowsA * 4, 16) + (size_t)NBUF * ((size_t)a.rowsA * kRowBytes + (size_t)3 * BN * kRowBytes);
+    if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
     if (lds > 160 * 1024) return VGG_ERR_UNSUPPORTED;
-    auto kern = conv3x3_igemm_kernel<T, BM, BN, WM, WN>;
+    auto kern = conv3x3_igemm_kernel<T, BM, BN, WM, WN, NBUF>;
     static bool configured = false;
     if (lds > 64 * 1024 && !configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -273,12 +333,16 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
     const bool narrow = Cout <= 64;
+    static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
     if (dtype == VGG_F32) {
-        return narrow ? launch_conv<float, 256, 64, 4, 1>(a, N, H, W, stream)
-                      : launch_conv<float, 256, 128, 4, 2>(a, N, H, W, stream);
+        if (narrow) return launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream);
+        if (variant == 1) return launch_conv<float, 256, 128, 4, 2, 2>(a, N, H, W, stream);
+        return launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
     }
-    return narrow ? launch_conv<bf16_t, 256, 64, 4, 1>(a, N, H, W, stream)
-                  : launch_conv<bf16_t, 256, 128, 4, 2>(a, N, H, W, stream);
+    if (narrow) return launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream);
+    if (variant == 1) return launch_conv<bf16_t, 256, 128, 4, 2, 2>(a, N, H, W, stream);
+    if (variant == 2) return launch_conv<bf16_t, 256, 128, 2, 2, 2>(a, N, H, W, stream);
+    return launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
 }
 
 }  // namespace vgg
