@@ -127,6 +127,13 @@ int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const voi
                     const void *w_packed, const float *bias, void *y_nhwc, int relu, void *ws,
                     size_t ws_bytes, void *stream);
 
+/* The network's first convolution (3 -> 64 channels), same definition as
+ * vgg_conv3x3_fwd, but x is the canonical NCHW fp32 image batch [N][3][H][W]
+ * and is read directly; y is NHWC [N][H][W][64] in `dtype`; w_packed is the
+ * forward packing for Cin = 3, Cout = 64 in `dtype`. */
+int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, const void *w_packed,
+                          const float *bias, void *y_nhwc, int relu, void *stream);
+
 /* dx[n,h,w,ci] = sum_{kh,kw,co} g[n,h-kh+1,w-kw+1,co] * w[co,ci,kh,kw]
  * (gradient with respect to the convolution's input; g is the gradient with
  * respect to its pre-activation output, zero outside the image).  w_tf is

@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["conv_igemm.hip", "conv_wgrad.hip", "pointwise.hip", "fc.hip", "api.hip"]
+SOURCES = ["conv_igemm.hip", "conv_first.hip", "conv_wgrad.hip", "pointwise.hip", "fc.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 LIB = os.path.join(HERE, "libvgg_mi355x.so")
@@ -26,7 +26,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB

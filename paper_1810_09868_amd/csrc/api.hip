@@ -7,6 +7,8 @@ namespace vgg {
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
                   const void *mask, void *y, int relu, hipStream_t stream);
+int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
+               int relu, hipStream_t stream);
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
 int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
                   hipStream_t stream);
@@ -186,12 +188,18 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
                  float *probs, bool want_probs, char *ws, bool training, hipStream_t s, Recorder &rec)
 {
     const int dt = c->dtype, N = c->N;
-    VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, P.cinp[0], x, ws + L.x0, s));
+    // Training keeps a channel-padded NHWC copy of the images (the first layer's weight gradient
+    // reads it); inference feeds the NCHW batch straight to the first convolution.
+    if (training) VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, P.cinp[0], x, ws + L.x0, s));
     const char *cur = ws + L.x0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         char *out = ws + L.act[l];
-        VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
-                                           reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr, out, 1, s));
+        if (l == 0 && !training)
+            VGG_STEP(rec, K_CONV, conv_first(dt, N, c->H, c->W, P.cinp[0], x, pk + P.conv_w[0],
+                                            reinterpret_cast<const float *>(pk + P.conv_b[0]), out, 1, s));
+        else
+            VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
+                                               reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr, out, 1, s));
         cur = out;
         if (pool_after(l)) {
             char *po = ws + L.pooled[l];
@@ -387,6 +395,16 @@ int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const voi
         x = ws;
     }
     return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, relu ? 1 : 0, s);
+}
+
+int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, const void *w, const float *bias, void *y,
+                          int relu, void *stream)
+{
+    if (!x_nchw || !w || !y) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (!conv_shape_ok(N, H, W, 3, 64)) return VGG_ERR_SHAPE;
+    if (!aligned16(x_nchw) || !aligned16(w) || !aligned16(y)) return VGG_ERR_ALIGN;
+    return conv_first(dtype, N, H, W, padded_channels(dtype, 3), x_nchw, w, bias, y, relu ? 1 : 0, (hipStream_t)stream);
 }
 
 size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)

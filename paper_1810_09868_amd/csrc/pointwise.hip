@@ -187,6 +187,19 @@ __global__ void nchw_to_nhwc_kernel(const float *__restrict__ x, T *__restrict__
     if (pix >= (size_t)N * HW) return;
     const size_t n = pix / HW, hw = pix % HW;
     T *o = y + pix * Cpad;
+    constexpr int V = 16 / (int)sizeof(T);
+    if (Cpad % V == 0) {
+        // 16-byte stores: V channels at a time
+        for (int c0 = 0; c0 < Cpad; c0 += V) {
+            T tmp[V];
+#pragma unroll
+            for (int k = 0; k < V; ++k) Elem<T>::store(tmp + k, c0 + k < C ? x[(n * C + c0 + k) * HW + hw] : 0.f);
+            f32x4 v;
+            __builtin_memcpy(&v, tmp, 16);
+            *reinterpret_cast<f32x4 *>(o + c0) = v;
+        }
+        return;
+    }
     for (int c = 0; c < Cpad; ++c) Elem<T>::store(o + c, c < C ? x[(n * C + c) * HW + hw] : 0.f);
 }
 

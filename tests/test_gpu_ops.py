@@ -53,6 +53,19 @@ def test_conv3x3_fwd(dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", [(2, 32, 48), (3, 20, 9), (1, 224, 224), (70, 16, 16)])
+def test_conv3x3_fwd_first_layer_from_nchw(dtype, shape):
+    N, H, W = shape
+    d = synth.conv_layer_inputs(N, H, W, 3, 64, seed=sum(shape))
+    y = torch.full((N, H, W, 64), float("nan"), dtype=TDT[dtype], device="cuda")
+    for relu in (1, 0):
+        ref = R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=bool(relu))
+        B.vgg_conv3x3_fwd_first(dtype, N, H, W, dev(d["x"]), _pack(dtype, d["w"]), dev(d["b"]), y, relu)
+        torch.cuda.synchronize()
+        assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
 def test_conv3x3_bwd_data(dtype, shape):
     N, H, W, Cin, Cout = shape
