@@ -83,7 +83,7 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
         "other_ms_per_step": other_ms,
         "per_layer": [{"layer": l, "ms": round(conv_ms[l], 4),
                        "tflops": round(conv_flops(N, l) / (conv_ms[l] * 1e-3) / 1e12, 1)} for l in range(16)],
-        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_kernel<%s,256,128,2,2>" % ("bf16" if dtype_name == "bf16" else "float"),
+        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_dma_kernel<%s,256,128,4,2>" % ("bf16" if dtype_name == "bf16" else "float"),
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "launches_per_step": len(wide), "avg_launch_ms": wide_ms, "traffic": None},
     }

@@ -65,6 +65,94 @@ template <> struct Mma<bf16_t> {
     }
 };
 
+// Epilogue shared by the kernels below; called by every thread of the workgroup once all MFMAs are
+// issued.  smem is the start of the workgroup's dynamic LDS, which is reused here.
+template <typename T, int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
+                                              const TileOrigin &org, char *smem, int n0)
+{
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int wm = wv % WM, wn = wv / WM;
+    const int r = lane & 31, khalf = lane >> 5;
+    // Epilogue: bias, ReLU, optional (mask > 0) factor, convert, store.
+    // 32x32 accumulator layout: register e of lane l holds row 8*(e/4) + 4*(l/32) + e%4, column l%32,
+    // i.e. a lane owns single elements of many rows.  Each wave transposes 32 rows x 128 bytes at a
+    // time through a private LDS block so that every lane stores 16 contiguous bytes of one pixel.
+    T *y = reinterpret_cast<T *>(p.y);
+    const T *mask = reinterpret_cast<const T *>(p.mask);
+    constexpr int VEC = 16 / (int)sizeof(T);        // elements per 16-byte store
+    constexpr int CPT = 128 / (int)sizeof(T);       // columns per transposed pass (64 bf16 / 32 fp32)
+    constexpr int TJ = CPT / 32;                    // MFMA column tiles per pass
+    static_assert(TN % TJ == 0, "wave tile must hold whole passes");
+    __syncthreads();  // staging data no longer needed: LDS is reused
+    if (p.Cout % VEC == 0) {
+        char *epi = smem + wv * kEpiBytes;
+        const int seg = lane & 7, rowq = lane >> 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j0 = 0; j0 < TN; j0 += TJ) {
+#pragma unroll
+                for (int jj = 0; jj < TJ; ++jj) {
+                    const int col = n0 + wn * (BN / WN) + (j0 + jj) * 32 + r;
+                    const float bv = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        float v = acc[i][j0 + jj][e] + bv;
+                        if (p.relu) v = fmaxf(v, 0.f);
+                        const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
+                        Elem<T>::store(reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r, v);
+                    }
+                }
+                const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = rowq + 8 * q;
+                    u32x4 v = *reinterpret_cast<const u32x4 *>(epi + row * kEpiRow + seg * 16);
+                    const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + row);
+                    if (m >= 0 && colbase < p.Cout) {
+                        const size_t o = (size_t)m * p.Cout + colbase;
+                        if (mask) {
+                            const u32x4 mk = *reinterpret_cast<const u32x4 *>(mask + o);
+                            T ve[VEC], me[VEC];
+                            __builtin_memcpy(ve, &v, 16);
+                            __builtin_memcpy(me, &mk, 16);
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k)
+                                if (!(Elem<T>::load(me + k) > 0.f)) ve[k] = (T)0;
+                            __builtin_memcpy(&v, ve, 16);
+                        }
+                        *reinterpret_cast<u32x4 *>(y + o) = v;
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // channel counts that do not allow 16-byte stores: element-wise
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3));
+            if (m < 0) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (BN / WN) + j * 32 + r;
+                if (col < p.Cout) {
+                    float v = acc[i][j][e] + (p.bias ? p.bias[col] : 0.f);
+                    if (p.relu) v = fmaxf(v, 0.f);
+                    const size_t o = (size_t)m * p.Cout + col;
+                    if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
+                    Elem<T>::store(y + o, v);
+                }
+            }
+        }
+    }
+}
+
 template <typename T, int BM, int BN, int WM, int WN, int NBUF>
 __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : 2) void conv3x3_igemm_kernel(ConvArgs p)
 {
@@ -220,81 +308,184 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : 2) void conv3x3_igemm_
     }
     compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
 
-    // Epilogue: bias, ReLU, optional (mask > 0) factor, convert, store.
-    // 32x32 accumulator layout: register e of lane l holds row 8*(e/4) + 4*(l/32) + e%4, column l%32,
-    // i.e. a lane owns single elements of many rows.  Each wave transposes 32 rows x 128 bytes at a
-    // time through a private LDS block so that every lane stores 16 contiguous bytes of one pixel.
-    T *y = reinterpret_cast<T *>(p.y);
-    const T *mask = reinterpret_cast<const T *>(p.mask);
-    constexpr int VEC = 16 / (int)sizeof(T);        // elements per 16-byte store
-    constexpr int CPT = 128 / (int)sizeof(T);       // columns per transposed pass (64 bf16 / 32 fp32)
-    constexpr int TJ = CPT / 32;                    // MFMA column tiles per pass
-    static_assert(TN % TJ == 0, "wave tile must hold whole passes");
-    __syncthreads();  // staging data no longer needed: LDS is reused
-    if (p.Cout % VEC == 0) {
-        char *epi = smem + wv * kEpiBytes;
-        const int seg = lane & 7, rowq = lane >> 3;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j0 = 0; j0 < TN; j0 += TJ) {
-#pragma unroll
-                for (int jj = 0; jj < TJ; ++jj) {
-                    const int col = n0 + wn * (BN / WN) + (j0 + jj) * 32 + r;
-                    const float bv = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        float v = acc[i][j0 + jj][e] + bv;
-                        if (p.relu) v = fmaxf(v, 0.f);
-                        const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
-                        Elem<T>::store(reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r, v);
-                    }
-                }
-                const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int row = rowq + 8 * q;
-                    u32x4 v = *reinterpret_cast<const u32x4 *>(epi + row * kEpiRow + seg * 16);
-                    const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + row);
-                    if (m >= 0 && colbase < p.Cout) {
-                        const size_t o = (size_t)m * p.Cout + colbase;
-                        if (mask) {
-                            const u32x4 mk = *reinterpret_cast<const u32x4 *>(mask + o);
-                            T ve[VEC], me[VEC];
-                            __builtin_memcpy(ve, &v, 16);
-                            __builtin_memcpy(me, &mk, 16);
-#pragma unroll
-                            for (int k = 0; k < VEC; ++k)
-                                if (!(Elem<T>::load(me + k) > 0.f)) ve[k] = (T)0;
-                            __builtin_memcpy(&v, ve, 16);
-                        }
-                        *reinterpret_cast<u32x4 *>(y + o) = v;
-                    }
-                }
-            }
-        }
-        return;
-    }
-    // channel counts that do not allow 16-byte stores: element-wise
+    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+}
+
+// ---------------------------------------------------------------------------
+// Variant with direct-to-LDS weight loads.  LDS rows are 64 bytes without
+// padding; the 16-byte segment s of row q lives at segment s ^ ((q >> 2) & 3),
+// which keeps the fragment reads of 16 consecutive rows on distinct banks.
+// The weights of a stage are copied by global_load_lds_dwordx4 (lane l of a
+// wave writes bytes [16 l, 16 l + 16) of a 1 KB block, so each lane fetches the
+// segment that belongs at its position) into one of two buffers while the
+// MFMAs of the previous stage run: no registers, no ds_write, one barrier per
+// stage.  The kernel waits for these loads itself (s_waitcnt vmcnt(0) before
+// the barrier that publishes a buffer).  The halo still goes through registers once per channel chunk.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+
+template <typename T, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvArgs p)
+{
+    constexpr int NT = WM * WN * 64, NW = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int KC = kDataBytes / (int)sizeof(T);
+    constexpr int MAXA = kMaxAHaloSegsPerBlock / NT;
+    constexpr int SA = kMaxAHaloSegsPerBlock / 4;   // halo rows (host guarantees S <= SA)
+    constexpr int b_bytes = 3 * BN * kDataBytes;
+    constexpr int NB = 3 * BN / 16 / NW;            // 1 KB blocks of a weight stage per wave
+    static_assert(3 * BN % (16 * NW) == 0 && BN % 16 == 0, "weight stage must split into whole 1 KB blocks");
+
+    extern __shared__ __align__(16) char smem[];
+    const int S = p.g.S;
+    int *pix = reinterpret_cast<int *>(smem);       // [SA]
+    char *As = smem + SA * 4;                        // [SA][64]
+    char *Bs = As + SA * kDataBytes;                 // [2][3*BN][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int wm = wv % WM, wn = wv / WM;
+    const int r = lane & 31, khalf = lane >> 5;
+    const int tile_n = blockIdx.x % p.tiles_n;
+    const int tile_m = blockIdx.x / p.tiles_n;
+    const int n0 = tile_n * BN;
+    const TileOrigin org = tile_origin(p.g, tile_m);
+    const int pitch = p.g.pitch;
+
+    for (int i = tid; i < SA; i += NT) pix[i] = i < S ? halo_pixel(p.g, org, i) : -1;
+
+    int arow[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        int m;
+        tile_row(p.g, org, wm * (BM / WM) + i * 32 + r, m, arow[i]);
+    }
+    int baddr[TN];  // k-group 0; k-group 1 is at ^32; tap kw adds kw*BN*64
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3));
-            if (m < 0) continue;
+    for (int j = 0; j < TN; ++j) {
+        const int row = wn * (BN / WN) + j * 32 + r;
+        baddr[j] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+    }
+
+    f32x16 acc[TM][TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * (BN / WN) + j * 32 + r;
-                if (col < p.Cout) {
-                    float v = acc[i][j][e] + (p.bias ? p.bias[col] : 0.f);
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    const size_t o = (size_t)m * p.Cout + col;
-                    if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
-                    Elem<T>::store(y + o, v);
-                }
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const size_t xrow = (size_t)p.CinP * sizeof(T);
+    const int nstages = (p.CinP / KC) * 3;
+
+    auto load_a = [&](int c0, u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < MAXA; ++j) {
+            const int idx = tid + j * NT;
+            const int off = pix[idx >> 2];
+            const char *src = off < 0 ? reinterpret_cast<const char *>(kZeroRow)
+                                      : p.x + (size_t)off * xrow + (size_t)c0 * sizeof(T);
+            areg[j] = *reinterpret_cast<const u32x4 *>(src + (idx & 3) * 16);
+        }
+    };
+    auto store_a = [&](const u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < MAXA; ++j) {
+            const int idx = tid + j * NT;
+            const int row = idx >> 2;
+            *reinterpret_cast<u32x4 *>(As + row * kDataBytes + (((idx & 3) ^ swz(row)) << 4)) = areg[j];
+        }
+    };
+    // this lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes
+    auto dma_b = [&](int c0, int kh, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int blk = wv * NB + q;
+            const int row = blk * 16 + (lane >> 2);          // kw*BN + n
+            const int kw = row / BN;
+            const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
+            const int seg = (lane & 3) ^ swz(row);
+            const char *src = p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + seg * 16;
+            // Issued as inline assembly on purpose: the compiler cannot tell that this write and the
+            // fragment reads of the other buffer never overlap and would wait for it before every read.
+            const unsigned dst = __builtin_amdgcn_readfirstlane(
+                (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + buf * b_bytes + blk * 1024));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0");
+        }
+    };
+    auto compute = [&](int kh, const char *Bt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            int aaddr[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = arow[i] + kh * pitch + kw;
+                aaddr[i] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+            }
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                uint4 af[TM], bf[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const uint4 *>(As + (aaddr[i] ^ (g * 32)));
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bf[j] = *reinterpret_cast<const uint4 *>(Bt + kw * BN * kDataBytes + (baddr[j] ^ (g * 32)));
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) Mma<T>::run(acc[i][j], af[i], bf[j]);
             }
         }
+    };
+
+    u32x4 areg[MAXA];
+    __syncthreads();  // halo table ready
+    dma_b(0, 0, 0);
+    load_a(0, areg);
+    store_a(areg);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
+    __syncthreads();
+
+    int kh = 0, c0 = 0, bb = 0;
+    for (int s = 0; s + 1 < nstages; ++s) {
+        int nkh = kh + 1, nc0 = c0;
+        if (nkh == 3) { nkh = 0; nc0 += KC; }
+        const bool new_chunk = nkh == 0;
+        dma_b(nc0, nkh, bb ^ 1);  // that buffer was last read two stages ago
+        if (new_chunk) load_a(nc0, areg);
+        compute(kh, Bs + bb * b_bytes);
+        if (new_chunk) {
+            __syncthreads();  // every wave is done reading the halo of this chunk
+            store_a(areg);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        kh = nkh; c0 = nc0; bb ^= 1;
     }
+    compute(kh, Bs + bb * b_bytes);
+
+    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t stream)
+{
+    ConvArgs a = a0;
+    a.g = g;
+    a.tiles_n = (a.Cout + BN - 1) / BN;
+    a.rowsA = kMaxAHaloSegsPerBlock / 4;
+    size_t lds = (size_t)a.rowsA * 4 + (size_t)a.rowsA * kDataBytes + (size_t)2 * 3 * BN * kDataBytes;
+    if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
+    auto kern = conv3x3_igemm_dma_kernel<T, BM, BN, WM, WN>;
+    static bool configured = false;
+    if (lds > 64 * 1024 && !configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                160 * 1024) != hipSuccess)
+            return VGG_ERR_LAUNCH;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n)), dim3(WM * WN * 64), lds, stream, a);
+    return launch_status();
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int NBUF>
@@ -333,16 +524,22 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
     const bool narrow = Cout <= 64;
+    // VGG_CONV_VARIANT=1 forces the register-staged kernel (for A/B measurements).
     static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
+    const TileGeom g = make_tile_geom(N, H, W, 256);
+    const bool dma = variant != 1 && g.S * 4 <= kMaxAHaloSegsPerBlock;
     if (dtype == VGG_F32) {
-        if (narrow) return launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream);
-        if (variant == 1) return launch_conv<float, 256, 128, 4, 2, 2>(a, N, H, W, stream);
-        return launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+        if (dma)
+            return narrow ? launch_conv_dma<float, 256, 64, 4, 1>(a, g, stream)
+                          : launch_conv_dma<float, 256, 128, 4, 2>(a, g, stream);
+        return narrow ? launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream)
+                      : launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
     }
-    if (narrow) return launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream);
-    if (variant == 1) return launch_conv<bf16_t, 256, 128, 4, 2, 2>(a, N, H, W, stream);
-    if (variant == 2) return launch_conv<bf16_t, 256, 128, 2, 2, 2>(a, N, H, W, stream);
-    return launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+    if (dma)
+        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1>(a, g, stream)
+                      : launch_conv_dma<bf16_t, 256, 128, 4, 2>(a, g, stream);
+    return narrow ? launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream)
+                  : launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
 }
 
 }  // namespace vgg
