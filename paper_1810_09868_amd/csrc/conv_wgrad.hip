@@ -31,7 +31,7 @@ struct WgradArgs {
     TileGeom geo;
 };
 
-__global__ __launch_bounds__(256) void conv3x3_wgrad_kernel(WgradArgs p)
+__global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
 {
     extern __shared__ __align__(16) char smem[];
     const int S = p.geo.S;
