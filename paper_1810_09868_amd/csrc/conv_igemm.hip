@@ -523,11 +523,14 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.y = static_cast<char *>(y);
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
-    const bool narrow = Cout <= 64;
+    bool narrow = Cout <= 64;
     // VGG_CONV_VARIANT=1 forces the register-staged kernel (for A/B measurements).
     static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
     const TileGeom g = make_tile_geom(N, H, W, 256);
     const bool dma = variant != 1 && g.S * 4 <= kMaxAHaloSegsPerBlock;
+    // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
+    // double the workgroup count and three of them fit on a CU.
+    if (g.ntiles * ((Cout + 127) / 128) < 512) narrow = true;
     if (dtype == VGG_F32) {
         if (dma)
             return narrow ? launch_conv_dma<float, 256, 64, 4, 1>(a, g, stream)
