@@ -20,7 +20,7 @@ NUM_CONV, NUM_FC = 16, 3
 EXPORTS = [
     "vgg_strerror", "vgg_padded_channels", "vgg_conv_pack_weights", "vgg_conv_unpack_weights",
     "vgg_nchw_to_nhwc", "vgg_nhwc_to_nchw", "vgg_convert",
-    "vgg_conv3x3_fwd_workspace_bytes", "vgg_conv3x3_fwd", "vgg_conv3x3_fwd_first",
+    "vgg_conv3x3_fwd_workspace_bytes", "vgg_conv3x3_fwd", "vgg_conv3x3_fwd_pool", "vgg_conv3x3_fwd_first",
     "vgg_conv3x3_bwd_data_workspace_bytes", "vgg_conv3x3_bwd_data",
     "vgg_conv3x3_bwd_weight_workspace_bytes", "vgg_conv3x3_bwd_weight",
     "vgg_maxpool2x2", "vgg_maxpool2x2_bwd",
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
             getattr(L, n).restype = _sz
             getattr(L, n).argtypes = [_i] * 6
         L.vgg_conv3x3_fwd.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
+        L.vgg_conv3x3_fwd_pool.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
         L.vgg_conv3x3_fwd_first.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _i, _vp]
         L.vgg_conv3x3_bwd_data.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.vgg_conv3x3_bwd_weight.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -170,6 +171,11 @@ def vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout) -> int:
 def vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, relu, ws=None):
     _chk(lib().vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(y), int(relu),
                                _ptr(ws), _nbytes(ws), _stream()), "vgg_conv3x3_fwd")
+
+
+def vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, pooled, relu, ws=None):
+    _chk(lib().vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(y), _ptr(pooled),
+                                    int(relu), _ptr(ws), _nbytes(ws), _stream()), "vgg_conv3x3_fwd_pool")
 
 
 def vgg_conv3x3_fwd_first(dtype, N, H, W, x_nchw, w_packed, bias, y, relu):

@@ -6,7 +6,8 @@
 namespace vgg {
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
-                  const void *mask, void *y, int relu, hipStream_t stream);
+                  const void *mask, void *y, void *pool, int relu, hipStream_t stream);
+bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
@@ -194,14 +195,21 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
     const char *cur = ws + L.x0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         char *out = ws + L.act[l];
+        // Inference on patch-tiled layers: the 2x2 maximum is taken in the convolution's epilogue and
+        // the un-pooled tensor is never written.
+        const bool fuse = !training && l > 0 && pool_after(l) && conv3x3_pool_fusable(dt, L.H[l], L.W[l], kConvCh[l][1]);
         if (l == 0 && !training)
             VGG_STEP(rec, K_CONV, conv_first(dt, N, c->H, c->W, P.cinp[0], x, pk + P.conv_w[0],
                                             reinterpret_cast<const float *>(pk + P.conv_b[0]), out, 1, s));
         else
             VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
-                                               reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr, out, 1, s));
+                                               reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr,
+                                               fuse ? nullptr : out, fuse ? ws + L.pooled[l] : nullptr, 1, s));
         cur = out;
-        if (pool_after(l)) {
+        if (fuse) {
+            rec.skip(K_POOL);  // fused into the launch above; listed so that the plan still shows five pools
+            cur = ws + L.pooled[l];
+        } else if (pool_after(l)) {
             char *po = ws + L.pooled[l];
             uint8_t *arg = training ? reinterpret_cast<uint8_t *>(ws + L.argmax[l]) : nullptr;
             VGG_STEP(rec, K_POOL, maxpool2x2(dt, N, L.H[l], L.W[l], kConvCh[l][1], cur, po, arg, s));
@@ -260,7 +268,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
             VGG_STEP(rec, K_OTHER, flip_packed_w(P.cinp[l], Cout, Cout, F(pk + P.conv_w[l]), F(ws + L.wflip), s));
             VGG_STEP(rec, K_DGRAD, conv3x3_igemm(VGG_F32, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
-                                                gbuf[cur ^ 1], 0, s));
+                                                gbuf[cur ^ 1], nullptr, 0, s));
             cur ^= 1;
         }
     }
@@ -378,13 +386,15 @@ size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, 
     return cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
 }
 
-int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
-                    void *y, int relu, void *ws, size_t ws_bytes, void *stream)
+static int conv_fwd_common(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
+                           void *y, void *pooled, int relu, void *ws, size_t ws_bytes, void *stream)
 {
-    if (!x || !w || !y) return VGG_ERR_NULL;
+    if (!x || !w || (!y && !pooled)) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
     if (!conv_shape_ok(N, H, W, Cin, Cout)) return VGG_ERR_SHAPE;
-    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
+    if (pooled && !conv3x3_pool_fusable(dtype, H, W, Cout)) return VGG_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w) || (y && !aligned16(y)) || (pooled && !aligned16(pooled)) || (ws && !aligned16(ws)))
+        return VGG_ERR_ALIGN;
     const size_t need = vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout);
     if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
     const int cp = padded_channels(dtype, Cin);
@@ -394,7 +404,21 @@ int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const voi
         if (rc) return rc;
         x = ws;
     }
-    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, relu ? 1 : 0, s);
+    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, pooled, relu ? 1 : 0, s);
+}
+
+int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
+                    void *y, int relu, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!y) return VGG_ERR_NULL;
+    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y, nullptr, relu, ws, ws_bytes, stream);
+}
+
+int vgg_conv3x3_fwd_pool(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
+                         void *y_or_null, void *pooled, int relu, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!pooled) return VGG_ERR_NULL;
+    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y_or_null, pooled, relu, ws, ws_bytes, stream);
 }
 
 int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, const void *w, const float *bias, void *y,
@@ -431,7 +455,7 @@ int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, cons
         if (rc) return rc;
         g = ws;
     }
-    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, 0, s);
+    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, nullptr, 0, s);
 }
 
 size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)

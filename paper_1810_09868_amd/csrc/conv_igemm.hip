@@ -36,7 +36,8 @@ struct ConvArgs {
     const char *w;      // [9][Cout][CinP]
     const float *bias;  // [Cout] or null
     const char *mask;   // [M][Cout] of T or null: output multiplied by (mask > 0)
-    char *y;            // [M][Cout]
+    char *y;            // [M][Cout], or null when only the pooled tensor is wanted
+    char *pool;         // [N][H/2][W/2][Cout] or null: 2x2 max of the result (patch tiles only)
     int CinP, Cout;
     int relu;
     int tiles_n;        // number of column tiles
@@ -107,6 +108,31 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
                     }
                 }
                 const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
+                if (p.pool) {
+                    // Patch tiles: these 32 rows are two patch rows of 16 pixels, i.e. eight whole 2x2
+                    // windows; lane = (window, 16-byte segment).  Window (dx) = rows 2dx, 2dx+1, 16+2dx, 17+2dx.
+                    const int win = lane >> 3;
+                    T best[VEC];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int row = (k >> 1) * kTileW + 2 * win + (k & 1);
+                        const u32x4 v = *reinterpret_cast<const u32x4 *>(epi + row * kEpiRow + seg * 16);
+                        T ve[VEC];
+                        __builtin_memcpy(ve, &v, 16);
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c)
+                            if (k == 0 || Elem<T>::load(ve + c) > Elem<T>::load(best + c)) best[c] = ve[c];
+                    }
+                    const int j = wm * (BM / WM) + i * 32;  // first tile row of this block (even patch row)
+                    const int ph = (org.h0 + j / kTileW) >> 1, pw = (org.w0 >> 1) + win;
+                    if (2 * ph < p.g.H && 2 * pw < p.g.W && colbase < p.Cout) {
+                        u32x4 v;
+                        __builtin_memcpy(&v, best, 16);
+                        T *po = reinterpret_cast<T *>(p.pool);
+                        *reinterpret_cast<u32x4 *>(po + (((size_t)org.n * (p.g.H >> 1) + ph) * (p.g.W >> 1) + pw) * p.Cout + colbase) = v;
+                    }
+                }
+                if (y == nullptr) continue;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int row = rowq + 8 * q;
@@ -512,15 +538,23 @@ static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stre
 }
 
 // x: [N*H*W][CinP], w: [9][Cout][CinP] (elements of dtype); y: [N*H*W][Cout].
-int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w,
-                  const float *bias, const void *mask, void *y, int relu, hipStream_t stream)
+// pool (optional): 2x2 max of y, only when conv3x3_pool_fusable(); y may then be null.
+bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout)
 {
+    return H % 16 == 0 && W % kTileW == 0 && Cout % (16 / dtype_size(dtype)) == 0;
+}
+
+int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w,
+                  const float *bias, const void *mask, void *y, void *pool, int relu, hipStream_t stream)
+{
+    if (pool && !conv3x3_pool_fusable(dtype, H, W, Cout)) return VGG_ERR_UNSUPPORTED;
     ConvArgs a;
     a.x = static_cast<const char *>(x);
     a.w = static_cast<const char *>(w);
     a.bias = bias;
     a.mask = static_cast<const char *>(mask);
     a.y = static_cast<char *>(y);
+    a.pool = static_cast<char *>(pool);
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
     bool narrow = Cout <= 64;

@@ -53,6 +53,32 @@ def test_conv3x3_fwd(dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", [(2, 32, 32, 64, 128), (3, 16, 48, 32, 64), (1, 112, 112, 32, 192)])
+def test_conv3x3_fwd_with_fused_pool(dtype, shape):
+    N, H, W, Cin, Cout = shape
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape) + 7)
+    x = to_nhwc(d["x"], dtype)
+    y = torch.full((N, H, W, Cout), float("nan"), dtype=TDT[dtype], device="cuda")
+    pooled = torch.full((N, H // 2, W // 2, Cout), float("nan"), dtype=TDT[dtype], device="cuda")
+    B.vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), y, pooled, 1)
+    torch.cuda.synchronize()
+    ref = R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=True)
+    pref, _ = R.maxpool2x2(ref)
+    assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
+    assert max_rel_err(from_nhwc(pooled), pref) <= TOL[dtype]
+    # the pooled tensor is exactly the 2x2 maximum of what the same launch wrote un-pooled
+    pgpu, _ = R.maxpool2x2(from_nhwc(y))
+    assert np.array_equal(from_nhwc(pooled), pgpu)
+    # un-pooled output suppressed
+    pooled2 = torch.empty_like(pooled)
+    B.vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), None, pooled2, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled2)
+    with pytest.raises(B.VggError):
+        B.vgg_conv3x3_fwd_pool(dtype, N, 14, 14, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), None, pooled2, 1)
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("shape", [(2, 32, 48), (3, 20, 9), (1, 224, 224), (70, 16, 16)])
 def test_conv3x3_fwd_first_layer_from_nchw(dtype, shape):
     N, H, W = shape
