@@ -68,8 +68,12 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
                 other_ms["other"] += t / steps
     total_conv_ms = sum(conv_ms)
     total_conv_flops = sum(conv_flops(N, l) for l in range(16))
-    # dominant kernel: the 128-channel-wide tile instantiation, used by every layer with Cout > 64
-    wide = [l for l in range(16) if CONV[l][1] > 64]
+    # dominant kernel: the 256x128-tile instantiation, used by every layer with Cout > 64 whose grid
+    # of such tiles can give each of the 256 CUs two workgroups (not the 14x14 layers)
+    def n_tiles(l):
+        hw = CONV[l][2]
+        return N * (hw // 16) ** 2 if hw % 16 == 0 else -(-N * hw * hw // 256)
+    wide = [l for l in range(16) if CONV[l][1] > 64 and n_tiles(l) * -(-CONV[l][1] // 128) >= 512]
     wide_flops = sum(conv_flops(N, l) for l in wide) / len(wide)       # algorithmic flops per launch
     wide_ms = sum(conv_ms[l] for l in wide) / len(wide)                # average launch duration
     achieved = wide_flops / (wide_ms * 1e-3) / 1e12
@@ -111,6 +115,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=4)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch one plain 256 MiB device copy (convert_kernel<float,float>, 2^26 elements) "
+                         "so that hardware byte counters can be scaled against a kernel of known traffic")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -122,6 +129,12 @@ def main():
     from paper_1810_09868_amd import binding as B
     from paper_1810_09868_amd import synth
     B.lib()
+    if a.pmc_calibration:
+        src = torch.zeros((1 << 26,), dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        B.vgg_convert(B.F32, B.F32, 1 << 26, src, dst)
+        torch.cuda.synchronize()
+        del src, dst
     inp = synth.full_config(a.batch, seed=0, with_labels=False)
     main_res = run_forward_bench(a.dtype, a.batch, a.steps, a.warmup, inp)
     out = {

@@ -30,6 +30,8 @@ constexpr int kDataBytes = 64;
 constexpr int kEpiRow = 144;              // epilogue transpose: 128 data bytes + 16 pad per row
 constexpr int kEpiBytes = 32 * kEpiRow;   // per wave
 constexpr int kMaxAHaloSegsPerBlock = 1536;  // 16-byte halo segments (384 rows) prefetched through registers
+constexpr int kDmaHaloRows = 384;            // halo rows of the direct-to-LDS kernel: 2 workgroups of 74 KB per CU
+constexpr int kDmaHaloRowsBig = 448;         // ... and of its variant for tiles that straddle images (78 KB)
 
 struct ConvArgs {
     const char *x;      // [M][CinP] elements of T
@@ -180,7 +182,7 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int NBUF>
-__global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : 2) void conv3x3_igemm_kernel(ConvArgs p)
+__global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)) void conv3x3_igemm_kernel(ConvArgs p)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;  // 32x32 MFMA tiles per wave along pixels
@@ -350,14 +352,16 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : 2) void conv3x3_igemm_
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
-template <typename T, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvArgs p)
+template <typename T, int BM, int BN, int WM, int WN, int SA>
+// (the second launch bound is the minimum number of waves per SIMD: two 8-wave or three 4-wave workgroups per CU)
+__global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igemm_dma_kernel(ConvArgs p)
 {
     constexpr int NT = WM * WN * 64, NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int KC = kDataBytes / (int)sizeof(T);
-    constexpr int MAXA = kMaxAHaloSegsPerBlock / NT;
-    constexpr int SA = kMaxAHaloSegsPerBlock / 4;   // halo rows (host guarantees S <= SA)
+    // SA: halo rows reserved in LDS (host guarantees S <= SA)
+    constexpr int SEGS = SA * 4;                    // 16-byte halo segments per chunk
+    constexpr int MAXA = (SEGS + NT - 1) / NT;      // of which each thread copies at most MAXA
     constexpr int b_bytes = 3 * BN * kDataBytes;
     constexpr int NB = 3 * BN / 16 / NW;            // 1 KB blocks of a weight stage per wave
     static_assert(3 * BN % (16 * NW) == 0 && BN % 16 == 0, "weight stage must split into whole 1 KB blocks");
@@ -372,8 +376,13 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvA
     const int lane = tid & 63, wv = tid >> 6;
     const int wm = wv % WM, wn = wv / WM;
     const int r = lane & 31, khalf = lane >> 5;
-    const int tile_n = blockIdx.x % p.tiles_n;
-    const int tile_m = blockIdx.x / p.tiles_n;
+    // Workgroup b runs on XCD b % 8 and every XCD has its own L2.  Renumber so that each XCD works
+    // through one contiguous range of (pixel tile, column tile) pairs: the column tiles of a pixel
+    // tile then share the halo, and neighbouring pixel tiles their overlap, in one L2.
+    const int nblk = gridDim.x, xcd = blockIdx.x & 7;
+    const int bid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + (blockIdx.x >> 3);
+    const int tile_n = bid % p.tiles_n;
+    const int tile_m = bid / p.tiles_n;
     const int n0 = tile_n * BN;
     const TileOrigin org = tile_origin(p.g, tile_m);
     const int pitch = p.g.pitch;
@@ -407,7 +416,7 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvA
     auto load_a = [&](int c0, u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < MAXA; ++j) {
-            const int idx = tid + j * NT;
+            const int idx = min(tid + j * NT, SEGS - 1);
             const int off = pix[idx >> 2];
             const char *src = off < 0 ? reinterpret_cast<const char *>(kZeroRow)
                                       : p.x + (size_t)off * xrow + (size_t)c0 * sizeof(T);
@@ -419,7 +428,8 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvA
         for (int j = 0; j < MAXA; ++j) {
             const int idx = tid + j * NT;
             const int row = idx >> 2;
-            *reinterpret_cast<u32x4 *>(As + row * kDataBytes + (((idx & 3) ^ swz(row)) << 4)) = areg[j];
+            if ((j + 1) * NT <= SEGS || idx < SEGS)
+                *reinterpret_cast<u32x4 *>(As + row * kDataBytes + (((idx & 3) ^ swz(row)) << 4)) = areg[j];
         }
     };
     // this lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes
@@ -493,16 +503,16 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_dma_kernel(ConvA
     conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
+template <typename T, int BM, int BN, int WM, int WN, int SA>
 static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t stream)
 {
     ConvArgs a = a0;
     a.g = g;
     a.tiles_n = (a.Cout + BN - 1) / BN;
-    a.rowsA = kMaxAHaloSegsPerBlock / 4;
+    a.rowsA = SA;
     size_t lds = (size_t)a.rowsA * 4 + (size_t)a.rowsA * kDataBytes + (size_t)2 * 3 * BN * kDataBytes;
     if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
-    auto kern = conv3x3_igemm_dma_kernel<T, BM, BN, WM, WN>;
+    auto kern = conv3x3_igemm_dma_kernel<T, BM, BN, WM, WN, SA>;
     static bool configured = false;
     if (lds > 64 * 1024 && !configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -561,20 +571,27 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     // VGG_CONV_VARIANT=1 forces the register-staged kernel (for A/B measurements).
     static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
     const TileGeom g = make_tile_geom(N, H, W, 256);
-    const bool dma = variant != 1 && g.S * 4 <= kMaxAHaloSegsPerBlock;
+    const bool dma = variant != 1 && g.S <= kDmaHaloRows;
+    const bool dma_big = variant != 1 && !dma && g.S <= kDmaHaloRowsBig;
     // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
     // double the workgroup count and three of them fit on a CU.
     if (g.ntiles * ((Cout + 127) / 128) < 512) narrow = true;
     if (dtype == VGG_F32) {
         if (dma)
-            return narrow ? launch_conv_dma<float, 256, 64, 4, 1>(a, g, stream)
-                          : launch_conv_dma<float, 256, 128, 4, 2>(a, g, stream);
+            return narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
+                          : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
+        if (dma_big)
+            return narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
+                          : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
         return narrow ? launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream)
                       : launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
     }
     if (dma)
-        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1>(a, g, stream)
-                      : launch_conv_dma<bf16_t, 256, 128, 4, 2>(a, g, stream);
+        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
+                      : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
+    if (dma_big)
+        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
+                      : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
     return narrow ? launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream)
                   : launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
 }
