@@ -29,6 +29,27 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 HBM_GBS = 8000.0
 
 
+def recorded_traffic(dtype_name, N):
+    """HBM-side bytes per launch of the roofline kernel from the committed rocprofv3 counter summary,
+    or None when there is none for this workload or the kernel sources changed since it was taken."""
+    import hashlib
+    import re
+    if N != 100:
+        return None
+    path = os.path.join(ROOT, "profiles", "vgg19_fwd_%s_batch100_rocprofv3.md" % dtype_name)
+    try:
+        text = open(path).read()
+        h = hashlib.sha256()
+        for fn in ("paper_1810_09868_amd/csrc/conv_igemm.hip", "paper_1810_09868_amd/csrc/common.h"):
+            h.update(open(os.path.join(ROOT, fn), "rb").read())
+        sha = re.search(r"kernel_source_sha256: ([0-9a-f]+)", text).group(1)
+        if sha != h.hexdigest():
+            return None
+        return float(re.search(r"traffic_bytes_per_launch: ([0-9.]+)", text).group(1))
+    except (OSError, AttributeError):
+        return None
+
+
 def conv_flops(N, l):
     ci, co, hw = CONV[l]
     return 2.0 * N * hw * hw * 9 * ci * co
@@ -87,9 +108,10 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
         "other_ms_per_step": other_ms,
         "per_layer": [{"layer": l, "ms": round(conv_ms[l], 4),
                        "tflops": round(conv_flops(N, l) / (conv_ms[l] * 1e-3) / 1e12, 1)} for l in range(16)],
-        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_dma_kernel<%s,256,128,4,2>" % ("bf16" if dtype_name == "bf16" else "float"),
+        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_dma_kernel<%s,256,128,4,2,*>" % ("bf16" if dtype_name == "bf16" else "float"),
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "launches_per_step": len(wide), "avg_launch_ms": wide_ms, "traffic": None},
+                     "launches_per_step": len(wide), "avg_launch_ms": wide_ms,
+                     "traffic": recorded_traffic(dtype_name, N)},
     }
     del m
     torch.cuda.empty_cache()
