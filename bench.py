@@ -118,6 +118,41 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
     return res
 
 
+def run_train_bench(N, steps, inp_seed=0):
+    """fp32 training step (forward, cross-entropy, backward, SGD) at the same shapes: extra context."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd import synth
+    from paper_1810_09868_amd.model import Vgg19
+    inp = synth.full_config(N, seed=inp_seed)
+    m = Vgg19(B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    x = torch.from_numpy(inp.x).cuda()
+    lab = torch.from_numpy(inp.labels).cuda()
+    for _ in range(2):
+        m.train_step(x, lab)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        m.train_step(x, lab)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    kinds, ms = B.vgg19_timed(m.cfg, True, x, lab, m.packed, m.logits, m.ws)
+    names = {1: "conv_fwd", 2: "conv_dgrad", 3: "conv_wgrad", 4: "pool", 5: "pool_bwd", 6: "fc", 7: "fc_bwd", 9: "other"}
+    by_kind = {}
+    for k, t in zip(kinds, ms):
+        if k in names:
+            by_kind[names[k]] = round(by_kind.get(names[k], 0.0) + t, 3)
+    conv = sum(conv_flops(N, l) for l in range(16))
+    fc = 2.0 * N * (25088 * 4096 + 4096 * 4096 + 4096 * 1000)
+    flops = 3 * conv - conv_flops(N, 0) + 3 * fc   # no data gradient for the first convolution
+    del m
+    torch.cuda.empty_cache()
+    return {"workload": "configs[4]: fp32 training step, batch %d, 3x224x224 (forward, mean cross-entropy, backward, SGD lr 0.01)" % N,
+            "dtype": "f32", "ms_per_step": dt * 1e3, "images_per_s": N / dt, "tflops": flops / dt / 1e12,
+            "pct_fp32_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS["f32"], "ms_by_kind": by_kind}
+
+
 def cpu_baseline(inp, images):
     from oracle import vgg_ref as R
     t0 = time.perf_counter()
@@ -136,7 +171,7 @@ def main():
     ap.add_argument("--batch", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
-    ap.add_argument("--cpu-images", type=int, default=4)
+    ap.add_argument("--cpu-images", type=int, default=24)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (convert_kernel<float,float>, 2^26 elements) "
                          "so that hardware byte counters can be scaled against a kernel of known traffic")
@@ -191,6 +226,8 @@ def main():
                             "dtype": other, "images_per_s": sec["images_per_s"], "ms_per_step": sec["ms_per_step"],
                             "conv_tflops": sec["conv_tflops"], "pct_mfma_peak_conv": sec["pct_mfma_peak_conv"],
                             "roofline": sec["roofline"]}
+    if not a.no_secondary:
+        out["train_step"] = run_train_bench(a.batch, max(2, a.steps // 5))
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, min(a.cpu_images, a.batch))
     print(json.dumps(out))
