@@ -103,7 +103,7 @@ struct TileOrigin {
     int m0, q0;     // LINEAR
 };
 
-__device__ __forceinline__ TileOrigin tile_origin(const TileGeom &g, int tile)
+__host__ __device__ __forceinline__ TileOrigin tile_origin(const TileGeom &g, int tile)
 {
     TileOrigin o;
     if (g.mode) {
@@ -123,7 +123,7 @@ __device__ __forceinline__ TileOrigin tile_origin(const TileGeom &g, int tile)
     return o;
 }
 
-__device__ __forceinline__ int halo_pixel(const TileGeom &g, const TileOrigin &o, int i)
+__host__ __device__ __forceinline__ int halo_pixel(const TileGeom &g, const TileOrigin &o, int i)
 {
     if (g.mode) {
         const int hy = i / (kTileW + 2), hx = i - hy * (kTileW + 2);
@@ -139,7 +139,7 @@ __device__ __forceinline__ int halo_pixel(const TileGeom &g, const TileOrigin &o
     return (n * g.H + h) * g.W + w;
 }
 
-__device__ __forceinline__ void tile_row(const TileGeom &g, const TileOrigin &o, int j, int &m, int &hrow)
+__host__ __device__ __forceinline__ void tile_row(const TileGeom &g, const TileOrigin &o, int j, int &m, int &hrow)
 {
     if (g.mode) {
         const int dy = j / kTileW, dx = j - dy * kTileW;
@@ -156,7 +156,7 @@ __device__ __forceinline__ void tile_row(const TileGeom &g, const TileOrigin &o,
 }
 
 // Output pixel of tile row j only (no halo row: no divisions).
-__device__ __forceinline__ int tile_pixel(const TileGeom &g, const TileOrigin &o, int j)
+__host__ __device__ __forceinline__ int tile_pixel(const TileGeom &g, const TileOrigin &o, int j)
 {
     if (g.mode) {
         const int h = o.h0 + j / kTileW, w = o.w0 + j % kTileW;
