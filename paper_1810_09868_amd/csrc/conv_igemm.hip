@@ -411,16 +411,20 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const size_t xrow = (size_t)p.CinP * sizeof(T);
-    const int nstages = (p.CinP / KC) * 3;
-
+    // Input pixel (or -1 for a pad row) behind each of this thread's halo segments; global, not
+    // generic, loads so that they neither touch the LDS counters nor look like LDS accesses.
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_t;
+    __syncthreads();  // halo table ready
+    int apix[MAXA];
+#pragma unroll
+    for (int j = 0; j < MAXA; ++j) apix[j] = pix[min(tid + j * NT, SEGS - 1) >> 2];
     auto load_a = [&](int c0, u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < MAXA; ++j) {
             const int idx = min(tid + j * NT, SEGS - 1);
-            const int off = pix[idx >> 2];
-            const char *src = off < 0 ? reinterpret_cast<const char *>(kZeroRow)
-                                      : p.x + (size_t)off * xrow + (size_t)c0 * sizeof(T);
-            areg[j] = *reinterpret_cast<const u32x4 *>(src + (idx & 3) * 16);
+            const gvec_t src = apix[j] < 0 ? (gvec_t)kZeroRow
+                                           : (gvec_t)(p.x + (size_t)apix[j] * xrow + (size_t)c0 * sizeof(T));
+            areg[j] = src[idx & 3];
         }
     };
     auto store_a = [&](const u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
             // fragment reads of the other buffer never overlap and would wait for it before every read.
             const unsigned dst = __builtin_amdgcn_readfirstlane(
                 (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + buf * b_bytes + blk * 1024));
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0", "memory");
         }
     };
     auto compute = [&](int kh, const char *Bt) __attribute__((always_inline)) {
@@ -475,26 +479,28 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     };
 
     u32x4 areg[MAXA];
-    __syncthreads();  // halo table ready
     dma_b(0, 0, 0);
     load_a(0, areg);
     store_a(areg);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
+    // Software pipeline over the stages.  Weight copies for the next stage go to the buffer that was
+    // last read two stages ago; the next chunk's halo is requested at the first stage of a chunk and
+    // stored to LDS after its last.
+    const int nstages = (p.CinP / KC) * 3;
     int kh = 0, c0 = 0, bb = 0;
     for (int s = 0; s + 1 < nstages; ++s) {
         int nkh = kh + 1, nc0 = c0;
         if (nkh == 3) { nkh = 0; nc0 += KC; }
-        const bool new_chunk = nkh == 0;
-        dma_b(nc0, nkh, bb ^ 1);  // that buffer was last read two stages ago
-        if (new_chunk) load_a(nc0, areg);
+        dma_b(nc0, nkh, bb ^ 1);
+        if (kh == 0 && c0 + KC < p.CinP) load_a(c0 + KC, areg);
         compute(kh, Bs + bb * b_bytes);
-        if (new_chunk) {
+        if (nkh == 0) {
             __syncthreads();  // every wave is done reading the halo of this chunk
             store_a(areg);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the weight copies have landed
         __syncthreads();
         kh = nkh; c0 = nc0; bb ^= 1;
     }
