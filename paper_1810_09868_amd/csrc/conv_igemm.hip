@@ -68,10 +68,23 @@ template <> struct Mma<bf16_t> {
     }
 };
 
+// Bias of this lane's accumulator columns.  Requested before the last stage's MFMAs so that the
+// epilogue never waits for a global load (which would also wait for every store issued before it).
+template <int BN, int WN, int TN>
+__device__ __forceinline__ void load_bias(float (&bv)[TN], const ConvArgs &p, int n0, int wn, int r)
+{
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * (BN / WN) + j * 32 + r;
+        bv[j] = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
+    }
+}
+
 // Epilogue shared by the kernels below; called by every thread of the workgroup once all MFMAs are
 // issued.  smem is the start of the workgroup's dynamic LDS, which is reused here.
 template <typename T, int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
+__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32],
+                                              const float (&bv)[BN / WN / 32], const ConvArgs &p,
                                               const TileOrigin &org, char *smem, int n0)
 {
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -93,20 +106,21 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
     if (p.Cout % VEC == 0) {
         char *epi = smem + wv * kEpiBytes;
         const int seg = lane & 7, rowq = lane >> 3;
+        const float lo = p.relu ? 0.f : -__builtin_inff();
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int j0 = 0; j0 < TN; j0 += TJ) {
 #pragma unroll
                 for (int jj = 0; jj < TJ; ++jj) {
-                    const int col = n0 + wn * (BN / WN) + (j0 + jj) * 32 + r;
-                    const float bv = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        float v = acc[i][j0 + jj][e] + bv;
-                        if (p.relu) v = fmaxf(v, 0.f);
+                    for (int e = 0; e < 16; e += 2) {
+                        // (no ReLU: maximum with -inf, one instruction either way)
+                        const float v0 = fmaxf(acc[i][j0 + jj][e] + bv[j0 + jj], lo);
+                        const float v1 = fmaxf(acc[i][j0 + jj][e + 1] + bv[j0 + jj], lo);
                         const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
-                        Elem<T>::store(reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r, v);
+                        T *dst = reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r;
+                        Elem<T>::store2(dst, dst + kEpiRow / (int)sizeof(T), v0, v1);
                     }
                 }
                 const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
@@ -170,7 +184,7 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + wn * (BN / WN) + j * 32 + r;
                 if (col < p.Cout) {
-                    float v = acc[i][j][e] + (p.bias ? p.bias[col] : 0.f);
+                    float v = acc[i][j][e] + bv[j];
                     if (p.relu) v = fmaxf(v, 0.f);
                     const size_t o = (size_t)m * p.Cout + col;
                     if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
@@ -334,9 +348,11 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
         __syncthreads();
         kh = nkh; c0 = nc0; ab = nab; bb = nbb;
     }
+    float bv[TN];
+    load_bias<BN, WN, TN>(bv, p, n0, wn, r);
     compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
 
-    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+    conv_epilogue<T, BM, BN, WM, WN>(acc, bv, p, org, smem, n0);
 }
 
 // ---------------------------------------------------------------------------
@@ -387,6 +403,25 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     const TileOrigin org = tile_origin(p.g, tile_m);
     const int pitch = p.g.pitch;
 
+    // this lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes
+    auto dma_b = [&](int c0, int kh, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int blk = wv * NB + q;
+            const int row = blk * 16 + (lane >> 2);          // kw*BN + n
+            const int kw = row / BN;
+            const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
+            const int seg = (lane & 3) ^ swz(row);
+            const char *src = p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + seg * 16;
+            // Issued as inline assembly on purpose: the compiler cannot tell that this write and the
+            // fragment reads of the other buffer never overlap and would wait for it before every read.
+            const unsigned dst = __builtin_amdgcn_readfirstlane(
+                (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + buf * b_bytes + blk * 1024));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0", "memory");
+        }
+    };
+    dma_b(0, 0, 0);  // first: its latency covers the index arithmetic below
+
     for (int i = tid; i < SA; i += NT) pix[i] = i < S ? halo_pixel(p.g, org, i) : -1;
 
     int arow[TM];
@@ -436,23 +471,6 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
                 *reinterpret_cast<u32x4 *>(As + row * kDataBytes + (((idx & 3) ^ swz(row)) << 4)) = areg[j];
         }
     };
-    // this lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes
-    auto dma_b = [&](int c0, int kh, int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < NB; ++q) {
-            const int blk = wv * NB + q;
-            const int row = blk * 16 + (lane >> 2);          // kw*BN + n
-            const int kw = row / BN;
-            const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
-            const int seg = (lane & 3) ^ swz(row);
-            const char *src = p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + seg * 16;
-            // Issued as inline assembly on purpose: the compiler cannot tell that this write and the
-            // fragment reads of the other buffer never overlap and would wait for it before every read.
-            const unsigned dst = __builtin_amdgcn_readfirstlane(
-                (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + buf * b_bytes + blk * 1024));
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0", "memory");
-        }
-    };
     auto compute = [&](int kh, const char *Bt) __attribute__((always_inline)) {
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
@@ -479,7 +497,6 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     };
 
     u32x4 areg[MAXA];
-    dma_b(0, 0, 0);
     load_a(0, areg);
     store_a(areg);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
@@ -504,9 +521,11 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
         __syncthreads();
         kh = nkh; c0 = nc0; bb ^= 1;
     }
+    float bv[TN];
+    load_bias<BN, WN, TN>(bv, p, n0, wn, r);
     compute(kh, Bs + bb * b_bytes);
 
-    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+    conv_epilogue<T, BM, BN, WM, WN>(acc, bv, p, org, smem, n0);
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int SA>

@@ -41,8 +41,33 @@ static long check(int N, int H, int W, int rows)
     return taps;
 }
 
+// fast_div against the division it replaces: every small divisor, a few large ones, numerators
+// around every multiple of the divisor they can reach plus the top of the 31-bit range.
+static bool check_fast_div()
+{
+    std::vector<int> ds;
+    for (int d = 1; d <= 3000; ++d) ds.push_back(d);
+    for (int d : {50176, 50177, 65535, 65536, 65537, 1000003, (1 << 30) - 1, 1 << 30, (1 << 30) + 1, 2147483647}) ds.push_back(d);
+    for (int d : ds) {
+        const FastDiv f = make_fast_div(d);
+        auto ok = [&](long long n) {
+            if (n < 0 || n > 2147483647ll) return true;
+            if (fast_div((int)n, f) != (int)(n / d)) { printf("fast_div(%lld, %d) = %d\n", n, d, fast_div((int)n, f)); return false; }
+            return true;
+        };
+        for (long long n = 0; n < 4096; ++n) if (!ok(n)) return false;
+        for (long long k = 1; k <= 2147483647ll / d; k += 1 + k / 7)
+            for (int e = -1; e <= 1; ++e) if (!ok(k * d + e)) return false;
+        const long long top = 2147483647ll / d * d;
+        for (int e = -2; e <= 2; ++e) if (!ok(top + e)) return false;
+        for (long long n = 2147483647ll - 64; n <= 2147483647ll; ++n) if (!ok(n)) return false;
+    }
+    return true;
+}
+
 int main()
 {
+    if (!check_fast_div()) return 1;
     const int shapes[][3] = {{2, 224, 224}, {3, 112, 112}, {5, 56, 56}, {7, 28, 28}, {100, 14, 14}, {9, 14, 14}, {3, 5, 7},
                              {1, 2, 2}, {4, 1, 1}, {2, 3, 300}, {2, 300, 3}, {5, 16, 48}, {1, 32, 32}, {2, 17, 16}, {1, 8, 16},
                              {3, 24, 16}};
