@@ -33,16 +33,10 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float *p) { return *p; }
     static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
-    static __device__ __forceinline__ void store2(float *p0, float *p1, float v0, float v1) { *p0 = v0; *p1 = v1; }
 };
 template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
     static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
-    static __device__ __forceinline__ void store2(bf16_t *p0, bf16_t *p1, float v0, float v1)
-    {
-        *p0 = f32_to_bf16(v0);
-        *p1 = f32_to_bf16(v1);
-    }
 };
 
 __device__ __forceinline__ float wave_sum(float v)

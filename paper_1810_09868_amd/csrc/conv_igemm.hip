@@ -68,23 +68,73 @@ template <> struct Mma<bf16_t> {
     }
 };
 
-// Bias of this lane's accumulator columns.  Requested before the last stage's MFMAs so that the
-// epilogue never waits for a global load (which would also wait for every store issued before it).
-template <int BN, int WN, int TN>
-__device__ __forceinline__ void load_bias(float (&bv)[TN], const ConvArgs &p, int n0, int wn, int r)
+// The MFMAs are issued with the weight fragment as the first operand, so a 32x32 accumulator holds
+// the tile transposed: register e of lane l is channel 8*(e/4) + 4*(l/32) + e%4 of pixel row l%32,
+// i.e. a lane owns runs of four consecutive channels of one pixel.
+//
+// Accumulators start at the bias, so the epilogue has no bias to fetch or add.  init_acc only
+// requests the values (into the first pixel block's registers).
+template <int BN, int WN, int TM, int TN>
+__device__ __forceinline__ void init_acc(f32x16 (&acc)[TM][TN], const ConvArgs &p, int n0, int wn, int khalf)
+{
+    // (channels past Cout are never stored: their loads are clamped into range instead of skipped;
+    // one uniform branch around straight-line loads, so that none of them waits for another)
+    const int c0 = n0 + wn * (BN / WN) + khalf * 4;
+    if (!p.bias) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
+    } else if ((p.Cout & 3) == 0) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const f32x4 b = *reinterpret_cast<const f32x4 *>(p.bias + min(c0 + j * 32 + a * 8, p.Cout - 4));
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[0][j][a * 4 + k] = b[k];
+            }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                acc[0][j][e] = p.bias[min(c0 + j * 32 + (e >> 2) * 8 + (e & 3), p.Cout - 1)];
+    }
+}
+// Second half, called once the loads above have had time to land: the other pixel blocks start
+// from the same values.
+template <int TM, int TN>
+__device__ __forceinline__ void spread_acc(f32x16 (&acc)[TM][TN])
 {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * (BN / WN) + j * 32 + r;
-        bv[j] = (p.bias && col < p.Cout) ? p.bias[col] : 0.f;
-    }
+    for (int i = 1; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = acc[0][j];
+}
+
+// Four values -> 16 bytes of fp32 or 8 bytes of bf16 (packed hardware conversion; the converted
+// vector is only ever reinterpreted whole).
+__device__ __forceinline__ void store4(float *dst, float v0, float v1, float v2, float v3)
+{
+    const f32x4 v = {v0, v1, v2, v3};
+    *reinterpret_cast<f32x4 *>(dst) = v;
+}
+__device__ __forceinline__ void store4(bf16_t *dst, float v0, float v1, float v2, float v3)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t lo = {v0, v1}, hi = {v2, v3};
+    const u32x2_t w = {__builtin_bit_cast(unsigned int, __builtin_convertvector(lo, bf16x2_t)),
+                       __builtin_bit_cast(unsigned int, __builtin_convertvector(hi, bf16x2_t))};
+    *reinterpret_cast<u32x2_t *>(dst) = w;
 }
 
 // Epilogue shared by the kernels below; called by every thread of the workgroup once all MFMAs are
 // issued.  smem is the start of the workgroup's dynamic LDS, which is reused here.
 template <typename T, int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32],
-                                              const float (&bv)[BN / WN / 32], const ConvArgs &p,
+__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
                                               const TileOrigin &org, char *smem, int n0)
 {
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -92,10 +142,9 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
     const int lane = tid & 63, wv = tid >> 6;
     const int wm = wv % WM, wn = wv / WM;
     const int r = lane & 31, khalf = lane >> 5;
-    // Epilogue: bias, ReLU, optional (mask > 0) factor, convert, store.
-    // 32x32 accumulator layout: register e of lane l holds row 8*(e/4) + 4*(l/32) + e%4, column l%32,
-    // i.e. a lane owns single elements of many rows.  Each wave transposes 32 rows x 128 bytes at a
-    // time through a private LDS block so that every lane stores 16 contiguous bytes of one pixel.
+    // Epilogue: ReLU, optional (mask > 0) factor, convert, store (the bias is already in the sums).
+    // A lane owns four-channel runs of one pixel (see init_acc).  Each wave passes 32 pixels x 128
+    // bytes at a time through a private LDS block so that every lane then stores 16 contiguous bytes.
     T *y = reinterpret_cast<T *>(p.y);
     const T *mask = reinterpret_cast<const T *>(p.mask);
     constexpr int VEC = 16 / (int)sizeof(T);        // elements per 16-byte store
@@ -114,13 +163,12 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
 #pragma unroll
                 for (int jj = 0; jj < TJ; ++jj) {
 #pragma unroll
-                    for (int e = 0; e < 16; e += 2) {
+                    for (int a = 0; a < 4; ++a) {
                         // (no ReLU: maximum with -inf, one instruction either way)
-                        const float v0 = fmaxf(acc[i][j0 + jj][e] + bv[j0 + jj], lo);
-                        const float v1 = fmaxf(acc[i][j0 + jj][e + 1] + bv[j0 + jj], lo);
-                        const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
-                        T *dst = reinterpret_cast<T *>(epi + row * kEpiRow) + jj * 32 + r;
-                        Elem<T>::store2(dst, dst + kEpiRow / (int)sizeof(T), v0, v1);
+                        const f32x16 &t = acc[i][j0 + jj];
+                        store4(reinterpret_cast<T *>(epi + r * kEpiRow) + jj * 32 + a * 8 + khalf * 4,
+                               fmaxf(t[a * 4], lo), fmaxf(t[a * 4 + 1], lo), fmaxf(t[a * 4 + 2], lo),
+                               fmaxf(t[a * 4 + 3], lo));
                     }
                 }
                 const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
@@ -176,15 +224,15 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
     // channel counts that do not allow 16-byte stores: element-wise
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + r);
+        if (m < 0) continue;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3));
-            if (m < 0) continue;
+        for (int j = 0; j < TN; ++j) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * (BN / WN) + j * 32 + r;
+            for (int e = 0; e < 16; ++e) {
+                const int col = n0 + wn * (BN / WN) + j * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
                 if (col < p.Cout) {
-                    float v = acc[i][j][e] + bv[j];
+                    float v = acc[i][j][e];
                     if (p.relu) v = fmaxf(v, 0.f);
                     const size_t o = (size_t)m * p.Cout + col;
                     if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
@@ -238,12 +286,7 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
     for (int j = 0; j < TN; ++j) bbase[j] = (wn * (BN / WN) + j * 32 + r) * kRowBytes + khalf * 16;
 
     f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    init_acc<BN, WN>(acc, p, n0, wn, khalf);
 
     const size_t xrow = (size_t)p.CinP * sizeof(T);
     const int nA = S * 4;  // 16-byte segments of the halo per chunk
@@ -306,6 +349,7 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
     load_b(0, 0, breg);
     store_b(breg, Bs);
     __syncthreads();
+    spread_acc(acc);
 
     auto compute = [&](int kh, const char *As, const char *Bs) __attribute__((always_inline)) {
 #pragma unroll
@@ -323,7 +367,7 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) Mma<T>::run(acc[i][j], af[i], bf[j]);
+                    for (int j = 0; j < TN; ++j) Mma<T>::run(acc[i][j], bf[j], af[i]);
             }
         }
     };
@@ -348,11 +392,9 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
         __syncthreads();
         kh = nkh; c0 = nc0; ab = nab; bb = nbb;
     }
-    float bv[TN];
-    load_bias<BN, WN, TN>(bv, p, n0, wn, r);
     compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
 
-    conv_epilogue<T, BM, BN, WM, WN>(acc, bv, p, org, smem, n0);
+    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
 // ---------------------------------------------------------------------------
@@ -438,27 +480,19 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     }
 
     f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    init_acc<BN, WN>(acc, p, n0, wn, khalf);
 
     const size_t xrow = (size_t)p.CinP * sizeof(T);
     // Input pixel (or -1 for a pad row) behind each of this thread's halo segments; global, not
     // generic, loads so that they neither touch the LDS counters nor look like LDS accesses.
     typedef const __attribute__((address_space(1))) u32x4 *gvec_t;
     __syncthreads();  // halo table ready
-    int apix[MAXA];
-#pragma unroll
-    for (int j = 0; j < MAXA; ++j) apix[j] = pix[min(tid + j * NT, SEGS - 1) >> 2];
     auto load_a = [&](int c0, u32x4(&areg)[MAXA]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < MAXA; ++j) {
             const int idx = min(tid + j * NT, SEGS - 1);
-            const gvec_t src = apix[j] < 0 ? (gvec_t)kZeroRow
-                                           : (gvec_t)(p.x + (size_t)apix[j] * xrow + (size_t)c0 * sizeof(T));
+            const int px = pix[idx >> 2];  // read again for every chunk: cheaper than MAXA registers held across the loop
+            const gvec_t src = px < 0 ? (gvec_t)kZeroRow : (gvec_t)(p.x + (size_t)px * xrow + (size_t)c0 * sizeof(T));
             areg[j] = src[idx & 3];
         }
     };
@@ -491,7 +525,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) Mma<T>::run(acc[i][j], af[i], bf[j]);
+                    for (int j = 0; j < TN; ++j) Mma<T>::run(acc[i][j], bf[j], af[i]);
             }
         }
     };
@@ -501,6 +535,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     store_a(areg);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
+    spread_acc(acc);
 
     // Software pipeline over the stages.  Weight copies for the next stage go to the buffer that was
     // last read two stages ago; the next chunk's halo is requested at the first stage of a chunk and
@@ -521,11 +556,9 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
         __syncthreads();
         kh = nkh; c0 = nc0; bb ^= 1;
     }
-    float bv[TN];
-    load_bias<BN, WN, TN>(bv, p, n0, wn, r);
     compute(kh, Bs + bb * b_bytes);
 
-    conv_epilogue<T, BM, BN, WM, WN>(acc, bv, p, org, smem, n0);
+    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int SA>
@@ -593,7 +626,8 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
     bool narrow = Cout <= 64;
-    // VGG_CONV_VARIANT=1 forces the register-staged kernel (for A/B measurements).
+    // For A/B measurements: VGG_CONV_VARIANT=1 forces the register-staged kernel, 2 the 64-wide
+    // column tiles, 3 the 128-wide ones.
     static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
     const TileGeom g = make_tile_geom(N, H, W, 256);
     const bool dma = variant != 1 && g.S <= kDmaHaloRows;
@@ -601,6 +635,8 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
     // double the workgroup count and three of them fit on a CU.
     if (g.ntiles * ((Cout + 127) / 128) < 512) narrow = true;
+    if (variant == 2) narrow = true;
+    if (variant == 3) narrow = false;
     if (dtype == VGG_F32) {
         if (dma)
             return narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
