@@ -5,21 +5,36 @@
 // (backward column of the appendix table: one more "convolution" per layer,
 // plus a "reduce" for the bias).  GEMM view per tap: rows = co, columns = ci,
 // contraction over the pixels m.  A workgroup owns a 64(co) x 32(ci) block of
-// all nine taps and a range of pixel tiles (split-K).  Per tile it stages the
-// g rows and the x halo (see TileGeom) in LDS; each of its four waves takes
-// one 32-row half of co and one half of the tile's pixels and issues nine
+// all nine taps and a range of pixel tiles (split-K).  Each of its four waves
+// takes one 32-row half of co and one half of a tile's pixels and issues nine
 // v_mfma_f32_32x32x2_f32 per pair of pixels, one per tap, all fed from the same
-// g fragment.  The two pixel-halves are added through LDS at the end and the
-// block writes its partial sums; a second kernel adds the partials of all
-// splits in a fixed order, so the result does not depend on scheduling.
+// g fragment.
+//
+// Staging: the g rows and the x halo (see TileGeom) of a tile are copied
+// straight into LDS by global_load_lds_dwordx4 (lane l of a wave writes bytes
+// [16 l, 16 l + 16) of a 1 KB block and supplies its own source address, so
+// rows outside the tensor simply read a block of zeros).  Two buffers: the
+// copies of tile k+1 are in flight while the MFMAs of tile k run, one barrier
+// per tile, no staging registers, no index tables (every lane derives the
+// pixels it needs from the tile geometry with a few multiplies).  Rows are
+// unpadded; the two pixels of an MFMA step sit in adjacent rows, which for
+// 128-byte x rows are already 32 banks apart, and for 256-byte g rows are made
+// so by swapping the two halves of every odd row.
+//
+// The two pixel-halves are added through LDS at the end and the block writes
+// its partial sums; a second kernel adds the partials of all splits in a fixed
+// order, so the result does not depend on scheduling.
 #include "common.h"
 
 namespace vgg {
 
-constexpr int kPK = 128;        // pixels per tile
+constexpr int kPK = 64;         // pixels per tile
 constexpr int kBCO = 64, kBCI = 32;
-constexpr int kGRow = kBCO * 4 + 16;  // bytes per LDS row of g (64 floats + pad)
-constexpr int kXRow = kBCI * 4 + 16;  // bytes per LDS row of x (32 floats + pad)
+constexpr int kGRow = kBCO * 4;  // bytes per LDS row of g
+constexpr int kXRow = kBCI * 4;  // bytes per LDS row of x
+
+typedef unsigned int wg_u32x4 __attribute__((ext_vector_type(4)));
+__device__ const wg_u32x4 kZeroSeg[1] = {};  // what a row outside the tensor reads
 
 struct WgradArgs {
     const float *x;   // [M][CinP]
@@ -28,18 +43,14 @@ struct WgradArgs {
     float *dbpart;    // [splits][Cout] or null
     int CinP, Cout;
     int tiles_co, tiles_ci, splits, tiles_per_split;
+    int SX;           // halo rows per buffer (geo.S rounded up to 8)
     TileGeom geo;
 };
 
 __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
 {
     extern __shared__ __align__(16) char smem[];
-    const int S = p.geo.S;
-    int *pix = reinterpret_cast<int *>(smem);            // [S]
-    int *rowm = pix + S;                                 // [kPK] output pixel of tile row or -1
-    int *rowh = rowm + kPK;                              // [kPK] halo row of tap (0,0)
-    char *Gs = smem + round_up16((S + 2 * kPK) * 4);     // [kPK][kGRow]
-    char *Xs = Gs + kPK * kGRow;                         // [S][kXRow]
+    const int buf_bytes = kPK * kGRow + p.SX * kXRow;   // [kPK][256] g rows, then [SX][128] x rows
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = lane & 31, kp = lane >> 5;
@@ -61,42 +72,81 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
 
     const int t_begin = split * p.tiles_per_split;
     const int t_end = min(t_begin + p.tiles_per_split, p.geo.ntiles);
+
+    // Index arithmetic is kept off the lanes' critical path: a wave-wide instruction costs several
+    // cycles whatever it computes, so every pixel index is derived once per tile by one lane and
+    // handed to the lanes that need it (ds_bpermute / v_readlane) instead of once per user.
+    //
+    // Direct-to-LDS copies of a wave: 1 KB block wv + 4k of the g rows (4 rows of 16 segments; odd
+    // rows hold their two halves swapped), k < kPK/16, and block wv + 4k of the x halo (8 rows of
+    // 8 segments), k < nxw.
+    constexpr int kGOps = kPK / 16;
+    const int nxw = ((p.SX >> 3) - wv + 3) >> 2;   // x blocks of this wave
+    const int gsub = lane >> 4;                                  // row of this lane within a g block
+    const int gcol = co0 + (((lane & 15) ^ ((gsub & 1) << 3)) << 2);
+    const bool gok = gcol < p.Cout;
+    const int xsub = lane >> 3;                                  // row of this lane within an x block
+    const int xcol = ci0 + ((lane & 7) << 2);
+    const bool xok = xcol < p.CinP;
+    const float *zero = reinterpret_cast<const float *>(kZeroSeg);
+    auto dma = [&](const float *src, char *dst) __attribute__((always_inline)) {
+        const unsigned d = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)dst);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(d), "v"(src) : "m0", "memory");
+    };
+    // m_l: output pixel of tile row `lane` (or -1), from tile_row
+    auto issue_tile = [&](const TileOrigin &org, char *base, int m_l) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kGOps; ++k) {
+            const int q = wv + 4 * k;
+            const int m = __shfl(m_l, q * 4 + gsub, kWave);
+            dma((gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero, base + q * 1024);
+        }
+        for (int k0 = 0; k0 < nxw; k0 += 8) {
+            // lane l looks up halo row (l & 7) of this wave's block k0 + (l >> 3)
+            const int kk = k0 + (lane >> 3);
+            const int i = (wv + 4 * kk) * 8 + (lane & 7);
+            const int px_l = (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
+            const int kn = min(nxw - k0, 8);
+            for (int k = 0; k < kn; ++k) {
+                const int px = __shfl(px_l, (k << 3) + xsub, kWave);
+                dma((xok && px >= 0) ? p.x + (size_t)px * p.CinP + xcol : zero,
+                    base + kPK * kGRow + (wv + 4 * (k0 + k)) * 1024);
+            }
+        }
+    };
+
+    const int wrow0 = __builtin_amdgcn_readfirstlane(wp * (kPK / 2));
+    int hrow_l = 0;  // halo row (tap 0,0) of tile row `lane` of the tile being multiplied
+    if (t_begin < t_end) {
+        const TileOrigin org0 = tile_origin(p.geo, t_begin);
+        int m_l;
+        tile_row(p.geo, org0, lane, m_l, hrow_l);
+        issue_tile(org0, smem, m_l);
+    }
     for (int tile = t_begin; tile < t_end; ++tile) {
-        const TileOrigin org = tile_origin(p.geo, tile);
-        __syncthreads();  // previous tile's reads done
-        for (int i = tid; i < S; i += 256) pix[i] = halo_pixel(p.geo, org, i);
-        for (int j = tid; j < kPK; j += 256) {
-            int m, hrow;
-            tile_row(p.geo, org, j, m, hrow);
-            rowm[j] = m;
-            rowh[j] = hrow;
-        }
+        const int buf = (tile - t_begin) & 1;
+        // This tile's copies have landed (each wave waits for its own, the barrier publishes all),
+        // and every wave is done with the other buffer, which the next copies overwrite.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();
-        // g rows: 64 floats = 16 segments of 16 bytes
-        for (int idx = tid; idx < kPK * 16; idx += 256) {
-            const int j = idx >> 4, seg = idx & 15;
-            const int m = rowm[j];
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m >= 0 && co0 + seg * 4 < p.Cout)
-                v = *reinterpret_cast<const uint4 *>(p.g + (size_t)m * p.Cout + co0 + seg * 4);
-            *reinterpret_cast<uint4 *>(Gs + j * kGRow + seg * 16) = v;
+        int hrow_next = 0;
+        if (tile + 1 < t_end) {
+            const TileOrigin orgn = tile_origin(p.geo, tile + 1);
+            int m_l;
+            tile_row(p.geo, orgn, lane, m_l, hrow_next);
+            issue_tile(orgn, smem + (buf ^ 1) * buf_bytes, m_l);
         }
-        // x halo rows: 32 floats = 8 segments
-        for (int idx = tid; idx < S * 8; idx += 256) {
-            const int i = idx >> 3, seg = idx & 7;
-            const int off = pix[i];
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (off >= 0 && ci0 + seg * 4 < p.CinP)
-                v = *reinterpret_cast<const uint4 *>(p.x + (size_t)off * p.CinP + ci0 + seg * 4);
-            *reinterpret_cast<uint4 *>(Xs + i * kXRow + seg * 16) = v;
-        }
-        __syncthreads();
-        // this wave: pixels [wp*64, wp*64+64) of the tile, two per MFMA step
-#pragma unroll 2
+
+        const char *Gs = smem + buf * buf_bytes;
+        const char *Xs = Gs + kPK * kGRow;
+        // this wave: pixels [wp*32, wp*32+32) of the tile, two per MFMA step
+        const char *ga = Gs + (wrow0 + kp) * kGRow + (((wc * 32 + r) ^ (kp << 5)) << 2);
+#pragma unroll 4
         for (int s = 0; s < kPK / 4; ++s) {
-            const int j = wp * (kPK / 2) + 2 * s + kp;
-            const float a = *reinterpret_cast<const float *>(Gs + j * kGRow + (wc * 32 + r) * 4);
-            const char *xb = Xs + rowh[j] * kXRow + r * 4;
+            const int h0 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s);
+            const int h1 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s + 1);
+            const float a = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
+            const char *xb = Xs + (kp ? h1 : h0) * kXRow + r * 4;
             gsum += a;
 #pragma unroll
             for (int kh = 0; kh < 3; ++kh)
@@ -106,6 +156,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
                     acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[kh * 3 + kw], 0, 0, 0);
                 }
         }
+        hrow_l = hrow_next;
     }
 
     // add the two pixel halves: waves with wp == 1 park their sums in LDS
@@ -154,6 +205,7 @@ __global__ void wgrad_reduce_kernel(const float *part, float *out, size_t n, int
 static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a)
 {
     a.geo = make_tile_geom(N, H, W, kPK);
+    a.SX = (a.geo.S + 7) & ~7;
     a.CinP = CinP; a.Cout = Cout;
     a.tiles_co = (Cout + kBCO - 1) / kBCO;
     a.tiles_ci = (CinP + kBCI - 1) / kBCI;
@@ -183,7 +235,7 @@ int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const
     a.part = static_cast<float *>(ws);
     a.dbpart = db ? reinterpret_cast<float *>(static_cast<char *>(ws) + round_up((size_t)a.splits * nw * 4, 256))
                   : nullptr;
-    size_t lds = round_up((size_t)(a.geo.S + 2 * kPK) * 4, 16) + (size_t)kPK * kGRow + (size_t)a.geo.S * kXRow;
+    size_t lds = (size_t)2 * (kPK * kGRow + a.SX * kXRow);
     const size_t red = (size_t)2 * 9 * 16 * 64 * 4 + 64 * 4;
     if (lds < red) lds = red;
     if (lds > 160 * 1024) return VGG_ERR_UNSUPPORTED;
