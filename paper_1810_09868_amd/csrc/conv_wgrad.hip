@@ -14,8 +14,8 @@
 // straight into LDS by global_load_lds_dwordx4 (lane l of a wave writes bytes
 // [16 l, 16 l + 16) of a 1 KB block and supplies its own source address, so
 // rows outside the tensor simply read a block of zeros).  Two buffers: the
-// copies of tile k+1 are in flight while the MFMAs of tile k run, one barrier
-// per tile, no staging registers, no index tables (every lane derives the
+// copies of tile k+1 are issued between, and in flight during, the MFMA steps of
+// tile k, one barrier per tile, no staging registers, no index tables (every lane derives the
 // pixels it needs from the tile geometry with a few multiplies).  Rows are
 // unpadded; the two pixels of an MFMA step sit in adjacent rows, which for
 // 128-byte x rows are already 32 banks apart, and for 256-byte g rows are made
@@ -93,35 +93,49 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
         const unsigned d = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)dst);
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(d), "v"(src) : "m0", "memory");
     };
-    // m_l: output pixel of tile row `lane` (or -1), from tile_row
-    auto issue_tile = [&](const TileOrigin &org, char *base, int m_l) __attribute__((always_inline)) {
-#pragma unroll
-        for (int k = 0; k < kGOps; ++k) {
-            const int q = wv + 4 * k;
-            const int m = __shfl(m_l, q * 4 + gsub, kWave);
-            dma((gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero, base + q * 1024);
-        }
-        for (int k0 = 0; k0 < nxw; k0 += 8) {
-            // lane l looks up halo row (l & 7) of this wave's block k0 + (l >> 3)
-            const int kk = k0 + (lane >> 3);
-            const int i = (wv + 4 * kk) * 8 + (lane & 7);
-            const int px_l = (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
-            const int kn = min(nxw - k0, 8);
-            for (int k = 0; k < kn; ++k) {
-                const int px = __shfl(px_l, (k << 3) + xsub, kWave);
-                dma((xok && px >= 0) ? p.x + (size_t)px * p.CinP + xcol : zero,
-                    base + kPK * kGRow + (wv + 4 * (k0 + k)) * 1024);
-            }
+    // Source addresses of a tile's copies.  m_l: output pixel of tile row `lane` (or -1).
+    constexpr int kXBatch = 8;                 // x blocks whose pixels one wave-wide lookup covers
+    constexpr int kOps = kGOps + kXBatch;      // copies that are spread over the MFMA steps
+    static_assert(kOps <= kPK / 4, "one copy per MFMA step");
+    auto g_src = [&](int m_l, int k) __attribute__((always_inline)) {
+        const int m = __shfl(m_l, (wv + 4 * k) * 4 + gsub, kWave);
+        return (gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero;
+    };
+    // lane l looks up halo row (l & 7) of this wave's x block k0 + (l >> 3)
+    auto x_lookup = [&](const TileOrigin &org, int k0) __attribute__((always_inline)) {
+        const int kk = k0 + (lane >> 3);
+        const int i = (wv + 4 * kk) * 8 + (lane & 7);
+        return (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
+    };
+    auto x_src = [&](int px_l, int k) __attribute__((always_inline)) {  // block k0 + k of the lookup px_l
+        const int px = __shfl(px_l, (k << 3) + xsub, kWave);
+        return (xok && px >= 0) ? p.x + (size_t)px * p.CinP + xcol : zero;
+    };
+    auto g_dst = [&](char *base, int k) __attribute__((always_inline)) { return base + (wv + 4 * k) * 1024; };
+    auto x_dst = [&](char *base, int k) __attribute__((always_inline)) {
+        return base + kPK * kGRow + (wv + 4 * k) * 1024;
+    };
+    // x blocks beyond the first batch (halos of more than 256 rows): issued in one go
+    auto issue_rest = [&](const TileOrigin &org, char *base) __attribute__((always_inline)) {
+        for (int k0 = kXBatch; k0 < nxw; k0 += kXBatch) {
+            const int px_l = x_lookup(org, k0);
+            const int kn = min(nxw - k0, kXBatch);
+            for (int k = 0; k < kn; ++k) dma(x_src(px_l, k), x_dst(base, k0 + k));
         }
     };
 
     const int wrow0 = __builtin_amdgcn_readfirstlane(wp * (kPK / 2));
+    const int nfirst = min(nxw, kXBatch);
     int hrow_l = 0;  // halo row (tap 0,0) of tile row `lane` of the tile being multiplied
     if (t_begin < t_end) {
         const TileOrigin org0 = tile_origin(p.geo, t_begin);
         int m_l;
         tile_row(p.geo, org0, lane, m_l, hrow_l);
-        issue_tile(org0, smem, m_l);
+#pragma unroll
+        for (int k = 0; k < kGOps; ++k) dma(g_src(m_l, k), g_dst(smem, k));
+        const int px_l = x_lookup(org0, 0);
+        for (int k = 0; k < nfirst; ++k) dma(x_src(px_l, k), x_dst(smem, k));
+        issue_rest(org0, smem);
     }
     for (int tile = t_begin; tile < t_end; ++tile) {
         const int buf = (tile - t_begin) & 1;
@@ -129,33 +143,68 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
         // and every wave is done with the other buffer, which the next copies overwrite.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();
+        // The next tile's copies are issued one per MFMA step.  Every workgroup of the launch works
+        // through its tiles at the same pace, so copies issued in one burst per tile meet in the
+        // memory system and the issuing waves wait there instead of multiplying.
+        // (index arithmetic at raised priority: next to a wave that streams MFMAs, an ordinary
+        // instruction otherwise waits behind every one of them)
+        __builtin_amdgcn_s_setprio(3);
+        const bool more = tile + 1 < t_end;
+        char *nbase = smem + (buf ^ 1) * buf_bytes;
         int hrow_next = 0;
-        if (tile + 1 < t_end) {
-            const TileOrigin orgn = tile_origin(p.geo, tile + 1);
-            int m_l;
+        const float *srcs[kOps];
+        TileOrigin orgn = tile_origin(p.geo, more ? tile + 1 : tile);
+        {
+            // all cross-lane reads first, then one wait: each of them has LDS latency
+            int m_l, mg[kGOps], pxs[kXBatch];
             tile_row(p.geo, orgn, lane, m_l, hrow_next);
-            issue_tile(orgn, smem + (buf ^ 1) * buf_bytes, m_l);
+            const int px_l = x_lookup(orgn, 0);
+#pragma unroll
+            for (int k = 0; k < kGOps; ++k)
+                mg[k] = __builtin_amdgcn_ds_bpermute(((wv + 4 * k) * 4 + gsub) << 2, m_l);
+#pragma unroll
+            for (int k = 0; k < kXBatch; ++k) pxs[k] = __builtin_amdgcn_ds_bpermute(((k << 3) + xsub) << 2, px_l);
+#pragma unroll
+            for (int k = 0; k < kGOps; ++k)
+                srcs[k] = (gok && mg[k] >= 0) ? p.g + (size_t)mg[k] * p.Cout + gcol : zero;
+#pragma unroll
+            for (int k = 0; k < kXBatch; ++k)
+                srcs[kGOps + k] = (xok && pxs[k] >= 0) ? p.x + (size_t)pxs[k] * p.CinP + xcol : zero;
         }
+        const int ncopy = more ? kGOps + nfirst : 0;
+        __builtin_amdgcn_s_setprio(0);
 
         const char *Gs = smem + buf * buf_bytes;
         const char *Xs = Gs + kPK * kGRow;
         // this wave: pixels [wp*32, wp*32+32) of the tile, two per MFMA step
         const char *ga = Gs + (wrow0 + kp) * kGRow + (((wc * 32 + r) ^ (kp << 5)) << 2);
-#pragma unroll 4
-        for (int s = 0; s < kPK / 4; ++s) {
+        // operands of step s+1 are read from LDS before the MFMAs of step s are issued
+        float a_next, b_next[9];
+        auto fetch = [&](int s) __attribute__((always_inline)) {
             const int h0 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s);
             const int h1 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s + 1);
-            const float a = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
+            a_next = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
             const char *xb = Xs + (kp ? h1 : h0) * kXRow + r * 4;
-            gsum += a;
 #pragma unroll
             for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
-                    const float bv = *reinterpret_cast<const float *>(xb + (kh * pitch + kw) * kXRow);
-                    acc[kh * 3 + kw] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[kh * 3 + kw], 0, 0, 0);
-                }
+                for (int kw = 0; kw < 3; ++kw)
+                    b_next[kh * 3 + kw] = *reinterpret_cast<const float *>(xb + (kh * pitch + kw) * kXRow);
+        };
+        fetch(0);
+#pragma unroll
+        for (int s = 0; s < kPK / 4; ++s) {
+            if (s < kOps && s < ncopy) dma(srcs[s], s < kGOps ? g_dst(nbase, s) : x_dst(nbase, s - kGOps));
+            const float a = a_next;
+            float bv[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) bv[t] = b_next[t];
+            if (s + 1 < kPK / 4) fetch(s + 1);
+            gsum += a;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[t], acc[t], 0, 0, 0);
         }
+        if (more) issue_rest(orgn, nbase);
         hrow_l = hrow_next;
     }
 
