@@ -5,10 +5,10 @@
 // (backward column of the appendix table: one more "convolution" per layer,
 // plus a "reduce" for the bias).  GEMM view per tap: rows = co, columns = ci,
 // contraction over the pixels m.  A workgroup owns a 64(co) x 32(ci) block of
-// all nine taps and a range of pixel tiles (split-K).  Each of its four waves
-// takes one 32-row half of co and one half of a tile's pixels and issues nine
-// v_mfma_f32_32x32x2_f32 per pair of pixels, one per tap, all fed from the same
-// g fragment.
+// all nine taps and a range of pixel tiles (split-K).  Each of its eight waves
+// takes one 32-row half of co, one half of a tile's pixels and five or four of
+// the taps, and issues one v_mfma_f32_32x32x2_f32 per tap and pair of pixels,
+// all fed from the same g fragment.
 //
 // Staging: the g rows and the x halo (see TileGeom) of a tile are copied
 // straight into LDS by global_load_lds_dwordx4 (lane l of a wave writes bytes
@@ -29,6 +29,7 @@
 namespace vgg {
 
 constexpr int kPK = 64;         // pixels per tile
+constexpr int kWaves = 8;
 constexpr int kBCO = 64, kBCI = 32;
 constexpr int kGRow = kBCO * 4;  // bytes per LDS row of g
 constexpr int kXRow = kBCI * 4;  // bytes per LDS row of x
@@ -47,14 +48,16 @@ struct WgradArgs {
     TileGeom geo;
 };
 
-__global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
+// Taps [T0, T0 + NT) of one wave: the main loop over the workgroup's tiles and the final sums.
+// S0: MFMA step before which the wave prepares the next tile's copies.
+template <int T0, int NT, int S0>
+__device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
 {
-    extern __shared__ __align__(16) char smem[];
     const int buf_bytes = kPK * kGRow + p.SX * kXRow;   // [kPK][256] g rows, then [SX][128] x rows
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = lane & 31, kp = lane >> 5;
-    const int wc = wv & 1, wp = wv >> 1;  // co half, pixel half
+    const int wc = wv & 1, wp = (wv >> 1) & 1;  // co half, pixel half (wv >> 2: tap group)
 
     int b = blockIdx.x;
     const int tco = b % p.tiles_co; b /= p.tiles_co;
@@ -63,9 +66,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
     const int co0 = tco * kBCO, ci0 = tci * kBCI;
     const int pitch = p.geo.pitch;
 
-    f32x16 acc[9];
+    f32x16 acc[NT];
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
     float gsum = 0.f;
@@ -77,11 +80,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
     // cycles whatever it computes, so every pixel index is derived once per tile by one lane and
     // handed to the lanes that need it (ds_bpermute / v_readlane) instead of once per user.
     //
-    // Direct-to-LDS copies of a wave: 1 KB block wv + 4k of the g rows (4 rows of 16 segments; odd
-    // rows hold their two halves swapped), k < kPK/16, and block wv + 4k of the x halo (8 rows of
+    // Direct-to-LDS copies of a wave: 1 KB block wv + 8k of the g rows (4 rows of 16 segments; odd
+    // rows hold their two halves swapped), k < kGOps, and block wv + 8k of the x halo (8 rows of
     // 8 segments), k < nxw.
-    constexpr int kGOps = kPK / 16;
-    const int nxw = ((p.SX >> 3) - wv + 3) >> 2;   // x blocks of this wave
+    constexpr int kGOps = kPK / 4 / kWaves;
+    const int nxw = ((p.SX >> 3) - wv + kWaves - 1) / kWaves;   // x blocks of this wave (SX >= 8 * kWaves)
     const int gsub = lane >> 4;                                  // row of this lane within a g block
     const int gcol = co0 + (((lane & 15) ^ ((gsub & 1) << 3)) << 2);
     const bool gok = gcol < p.Cout;
@@ -93,33 +96,33 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
         const unsigned d = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)dst);
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(d), "v"(src) : "m0", "memory");
     };
-    // Source addresses of a tile's copies.  m_l: output pixel of tile row `lane` (or -1).
-    constexpr int kXBatch = 8;                 // x blocks whose pixels one wave-wide lookup covers
+    constexpr int kXBatch = 3;                 // x blocks of a wave whose copies are spread over the steps
     constexpr int kOps = kGOps + kXBatch;      // copies that are spread over the MFMA steps
-    static_assert(kOps <= kPK / 4, "one copy per MFMA step");
-    auto g_src = [&](int m_l, int k) __attribute__((always_inline)) {
-        const int m = __shfl(m_l, (wv + 4 * k) * 4 + gsub, kWave);
-        return (gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero;
-    };
-    // lane l looks up halo row (l & 7) of this wave's x block k0 + (l >> 3)
+    static_assert(S0 + kOps <= kPK / 4, "one copy per MFMA step");
+    // lane l looks up halo row (l & 7) of this wave's x block k0 + (l >> 3) (blocks k0 .. k0 + 7)
     auto x_lookup = [&](const TileOrigin &org, int k0) __attribute__((always_inline)) {
         const int kk = k0 + (lane >> 3);
-        const int i = (wv + 4 * kk) * 8 + (lane & 7);
+        const int i = (wv + kWaves * kk) * 8 + (lane & 7);
         return (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
     };
-    auto x_src = [&](int px_l, int k) __attribute__((always_inline)) {  // block k0 + k of the lookup px_l
-        const int px = __shfl(px_l, (k << 3) + xsub, kWave);
+    // source addresses of g copy k / of x copy k of a lookup; m_l: output pixel of tile row `lane`
+    auto g_src = [&](int m_l, int k) __attribute__((always_inline)) {
+        const int m = __builtin_amdgcn_ds_bpermute(((wv + kWaves * k) * 4 + gsub) << 2, m_l);
+        return (gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero;
+    };
+    auto x_src = [&](int px_l, int k) __attribute__((always_inline)) {
+        const int px = __builtin_amdgcn_ds_bpermute(((k << 3) + xsub) << 2, px_l);
         return (xok && px >= 0) ? p.x + (size_t)px * p.CinP + xcol : zero;
     };
-    auto g_dst = [&](char *base, int k) __attribute__((always_inline)) { return base + (wv + 4 * k) * 1024; };
+    auto g_dst = [&](char *base, int k) __attribute__((always_inline)) { return base + (wv + kWaves * k) * 1024; };
     auto x_dst = [&](char *base, int k) __attribute__((always_inline)) {
-        return base + kPK * kGRow + (wv + 4 * k) * 1024;
+        return base + kPK * kGRow + (wv + kWaves * k) * 1024;
     };
-    // x blocks beyond the first batch (halos of more than 256 rows): issued in one go
+    // x blocks beyond the first batch (large halos): issued in one go
     auto issue_rest = [&](const TileOrigin &org, char *base) __attribute__((always_inline)) {
-        for (int k0 = kXBatch; k0 < nxw; k0 += kXBatch) {
+        for (int k0 = kXBatch; k0 < nxw; k0 += 8) {
             const int px_l = x_lookup(org, k0);
-            const int kn = min(nxw - k0, kXBatch);
+            const int kn = min(nxw - k0, 8);
             for (int k = 0; k < kn; ++k) dma(x_src(px_l, k), x_dst(base, k0 + k));
         }
     };
@@ -143,66 +146,56 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
         // and every wave is done with the other buffer, which the next copies overwrite.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         __syncthreads();
-        // The next tile's copies are issued one per MFMA step.  Every workgroup of the launch works
-        // through its tiles at the same pace, so copies issued in one burst per tile meet in the
-        // memory system and the issuing waves wait there instead of multiplying.
-        // (index arithmetic at raised priority: next to a wave that streams MFMAs, an ordinary
-        // instruction otherwise waits behind every one of them)
-        __builtin_amdgcn_s_setprio(3);
+        // The next tile's copies are issued one per MFMA step rather than in a burst, and their
+        // addresses are prepared before step S0: all waves of all workgroups on a CU run in
+        // lockstep, so if every wave did this at the same point the MFMA pipes would idle meanwhile.
         const bool more = tile + 1 < t_end;
         char *nbase = smem + (buf ^ 1) * buf_bytes;
         int hrow_next = 0;
         const float *srcs[kOps];
-        TileOrigin orgn = tile_origin(p.geo, more ? tile + 1 : tile);
-        {
+        TileOrigin orgn;
+        const int ncopy = more ? kGOps + nfirst : 0;
+        auto prepare = [&]() __attribute__((always_inline)) {
             // all cross-lane reads first, then one wait: each of them has LDS latency
-            int m_l, mg[kGOps], pxs[kXBatch];
+            orgn = tile_origin(p.geo, more ? tile + 1 : tile);
+            int m_l;
             tile_row(p.geo, orgn, lane, m_l, hrow_next);
             const int px_l = x_lookup(orgn, 0);
 #pragma unroll
-            for (int k = 0; k < kGOps; ++k)
-                mg[k] = __builtin_amdgcn_ds_bpermute(((wv + 4 * k) * 4 + gsub) << 2, m_l);
+            for (int k = 0; k < kGOps; ++k) srcs[k] = g_src(m_l, k);
 #pragma unroll
-            for (int k = 0; k < kXBatch; ++k) pxs[k] = __builtin_amdgcn_ds_bpermute(((k << 3) + xsub) << 2, px_l);
-#pragma unroll
-            for (int k = 0; k < kGOps; ++k)
-                srcs[k] = (gok && mg[k] >= 0) ? p.g + (size_t)mg[k] * p.Cout + gcol : zero;
-#pragma unroll
-            for (int k = 0; k < kXBatch; ++k)
-                srcs[kGOps + k] = (xok && pxs[k] >= 0) ? p.x + (size_t)pxs[k] * p.CinP + xcol : zero;
-        }
-        const int ncopy = more ? kGOps + nfirst : 0;
-        __builtin_amdgcn_s_setprio(0);
+            for (int k = 0; k < kXBatch; ++k) srcs[kGOps + k] = x_src(px_l, k);
+        };
 
         const char *Gs = smem + buf * buf_bytes;
         const char *Xs = Gs + kPK * kGRow;
         // this wave: pixels [wp*32, wp*32+32) of the tile, two per MFMA step
         const char *ga = Gs + (wrow0 + kp) * kGRow + (((wc * 32 + r) ^ (kp << 5)) << 2);
         // operands of step s+1 are read from LDS before the MFMAs of step s are issued
-        float a_next, b_next[9];
+        float a_next, b_next[NT];
         auto fetch = [&](int s) __attribute__((always_inline)) {
             const int h0 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s);
             const int h1 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s + 1);
             a_next = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
             const char *xb = Xs + (kp ? h1 : h0) * kXRow + r * 4;
 #pragma unroll
-            for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-                for (int kw = 0; kw < 3; ++kw)
-                    b_next[kh * 3 + kw] = *reinterpret_cast<const float *>(xb + (kh * pitch + kw) * kXRow);
+            for (int t = 0; t < NT; ++t)
+                b_next[t] = *reinterpret_cast<const float *>(xb + (((T0 + t) / 3) * pitch + (T0 + t) % 3) * kXRow);
         };
         fetch(0);
 #pragma unroll
         for (int s = 0; s < kPK / 4; ++s) {
-            if (s < kOps && s < ncopy) dma(srcs[s], s < kGOps ? g_dst(nbase, s) : x_dst(nbase, s - kGOps));
+            if (s == S0) prepare();
+            if (s >= S0 && s - S0 < kOps && s - S0 < ncopy)
+                dma(srcs[s - S0], s - S0 < kGOps ? g_dst(nbase, s - S0) : x_dst(nbase, s - S0 - kGOps));
             const float a = a_next;
-            float bv[9];
+            float bv[NT];
 #pragma unroll
-            for (int t = 0; t < 9; ++t) bv[t] = b_next[t];
+            for (int t = 0; t < NT; ++t) bv[t] = b_next[t];
             if (s + 1 < kPK / 4) fetch(s + 1);
             gsum += a;
 #pragma unroll
-            for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[t], acc[t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[t], acc[t], 0, 0, 0);
         }
         if (more) issue_rest(orgn, nbase);
         hrow_l = hrow_next;
@@ -213,33 +206,45 @@ __global__ __launch_bounds__(256, 2) void conv3x3_wgrad_kernel(WgradArgs p)
     float *red = reinterpret_cast<float *>(smem);  // needs 2 * 9*16*64 floats = 73728 bytes
     if (wp == 1) {
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) red[((wc * 9 + t) * 16 + e) * 64 + lane] = acc[t][e];
+            for (int e = 0; e < 16; ++e) red[((wc * 9 + T0 + t) * 16 + e) * 64 + lane] = acc[t][e];
     }
     __syncthreads();
     float gs_other = __shfl_xor(gsum, 32, kWave);  // the other pixel of the pair
     gsum += gs_other;
     float *dbs = reinterpret_cast<float *>(smem) + 2 * 9 * 16 * 64;  // [2][32]
-    if (wp == 1 && kp == 0) dbs[wc * 32 + r] = gsum;
+    if (T0 == 0 && wp == 1 && kp == 0) dbs[wc * 32 + r] = gsum;
     if (wp == 0) {
         // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (co), column l%32 (ci)
         const int ci = ci0 + r;
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int co = co0 + wc * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                const float v = acc[t][e] + red[((wc * 9 + t) * 16 + e) * 64 + lane];
+                const float v = acc[t][e] + red[((wc * 9 + T0 + t) * 16 + e) * 64 + lane];
                 if (co < p.Cout && ci < p.CinP)
-                    p.part[(((size_t)split * 9 + t) * p.Cout + co) * p.CinP + ci] = v;
+                    p.part[(((size_t)split * 9 + T0 + t) * p.Cout + co) * p.CinP + ci] = v;
             }
     }
     __syncthreads();
-    if (p.dbpart && tci == 0 && wp == 0 && kp == 0) {
+    if (T0 == 0 && p.dbpart && tci == 0 && wp == 0 && kp == 0) {
         const int co = co0 + wc * 32 + r;
         if (co < p.Cout) p.dbpart[(size_t)split * p.Cout + co] = gsum + dbs[wc * 32 + r];
     }
+}
+
+// Eight waves: (co half) x (pixel half) x (taps 0-4 | taps 5-8).  Splitting the taps halves the
+// accumulator registers of a wave, so four waves fit on a SIMD; a wave of each tap group lands on
+// every SIMD (wave w runs on SIMD w % 4), which balances the 5:4 split; the two groups also prepare
+// the next tile at different points of a tile, so a SIMD always has waves that are multiplying.
+__global__ __launch_bounds__(kWaves * 64, 4) void conv3x3_wgrad_kernel(WgradArgs p)
+{
+    extern __shared__ __align__(16) char smem[];
+    // (wave-uniform branch: both bodies execute the same sequence of barriers)
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 8) == 0) wgrad_body<0, 5, 0>(p, smem);
+    else wgrad_body<5, 4, kPK / 8>(p, smem);
 }
 
 __global__ void wgrad_reduce_kernel(const float *part, float *out, size_t n, int splits)
@@ -255,6 +260,7 @@ static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a)
 {
     a.geo = make_tile_geom(N, H, W, kPK);
     a.SX = (a.geo.S + 7) & ~7;
+    if (a.SX < 8 * kWaves) a.SX = 8 * kWaves;  // every wave copies at least one halo block
     a.CinP = CinP; a.Cout = Cout;
     a.tiles_co = (Cout + kBCO - 1) / kBCO;
     a.tiles_ci = (CinP + kBCI - 1) / kBCI;
@@ -295,7 +301,7 @@ int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const
             return VGG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3((unsigned)(a.tiles_co * a.tiles_ci * a.splits)), dim3(256), lds,
+    hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3((unsigned)(a.tiles_co * a.tiles_ci * a.splits)), dim3(kWaves * 64), lds,
                        stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, stream, a.part, dw, nw,
