@@ -39,6 +39,24 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Four values -> 16 bytes of fp32 or 8 bytes of bf16 (packed hardware conversion; the converted
+// vector is only ever reinterpreted whole).
+__device__ __forceinline__ void store4(float *dst, float v0, float v1, float v2, float v3)
+{
+    const f32x4 v = {v0, v1, v2, v3};
+    *reinterpret_cast<f32x4 *>(dst) = v;
+}
+__device__ __forceinline__ void store4(bf16_t *dst, float v0, float v1, float v2, float v3)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t lo = {v0, v1}, hi = {v2, v3};
+    const u32x2_t w = {__builtin_bit_cast(unsigned int, __builtin_convertvector(lo, bf16x2_t)),
+                       __builtin_bit_cast(unsigned int, __builtin_convertvector(hi, bf16x2_t))};
+    *reinterpret_cast<u32x2_t *>(dst) = w;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

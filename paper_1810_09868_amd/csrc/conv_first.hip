@@ -5,11 +5,16 @@
 // (appendix table row "convolution", first of 16); padding the image to a
 // full channel row and running the general kernel would read and write an
 // extra padded copy of the batch.  Here a workgroup stages the 3 x 18 x 18
-// fp32 halo of a 16 x 16 pixel patch in LDS, every lane gathers its A
-// operand (pixel row, 8 or 1 contraction indices) from that halo, the B
-// operand (the whole 27 x 64 filter bank) lives in registers, and the result
-// goes through the same LDS transpose as the general kernel so that each
-// lane stores 16 contiguous bytes.  Contraction index k = 3*tap + ci.
+// fp32 halo of a 16 x 16 pixel patch in LDS (the next patch's halo is already
+// in registers while the current one is multiplied), every lane gathers its
+// pixel operand (pixel row, 8 or 1 contraction indices) from that halo, and
+// the whole filter bank lives in registers.  Contraction index k = 3*tap + ci;
+// the indices 27 (and 28 for bf16) that pad the contraction to a multiple of
+// the MFMA depth carry the bias: the pixel operand is 1 there and the filter
+// operand the bias (for bf16 split into a rounded value and its remainder), so
+// the matrix pipe adds it.  The MFMAs take the filter fragment first, so a lane
+// ends up with runs of four consecutive channels of one pixel; those go through
+// a per-wave LDS block so that each lane stores 16 contiguous bytes.
 #include "common.h"
 
 namespace vgg {
@@ -19,6 +24,8 @@ typedef unsigned int u32x4f __attribute__((ext_vector_type(4)));
 constexpr int kFirstCout = 64;
 constexpr int kHaloW = 20;                       // 18 columns + 2 pad floats per halo row
 constexpr int kHaloFloats = 3 * 18 * kHaloW;
+constexpr int kHaloElems = 3 * 18 * 18;
+constexpr int kHaloPerThread = (kHaloElems + 255) / 256;
 constexpr int kFirstEpiRow = 144, kFirstEpiBytes = 32 * kFirstEpiRow;
 
 // float offset inside the staged halo of contraction index k for the pixel at halo origin
@@ -33,22 +40,27 @@ struct FirstArgs {
     const float *bias;  // [64]
     char *y;            // [N][H][W][64] in T
     int N, H, W, CinP, relu, tiles_w, tiles_hw, ntiles;
+    FastDiv dTilesW, dTilesHW;
 };
 
 template <typename T>
-__global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
+__global__ __launch_bounds__(256, 3) void conv_first_kernel(FirstArgs p)
 {
     __shared__ float xs[kHaloFloats];
     __shared__ __align__(16) char epi_all[4 * kFirstEpiBytes];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = lane & 31, khalf = lane >> 5;
     const T *wp = reinterpret_cast<const T *>(p.w);
-    auto wval = [&](int k, int co) -> float {  // filter value for contraction index k, output channel co
-        return k < 27 ? Elem<T>::load(wp + ((size_t)(k / 3) * kFirstCout + co) * p.CinP + k % 3) : 0.f;
-    };
-    // The whole filter bank as B operands, loaded once per workgroup and kept in registers.
     constexpr bool kBf16 = sizeof(T) == 2;
-    constexpr int NSTEP = kBf16 ? 2 : 14;
+    // filter operand for contraction index k, output channel co (bias at the padding indices)
+    auto wval = [&](int k, int co) -> float {
+        if (k < 27) return Elem<T>::load(wp + ((size_t)(k / 3) * kFirstCout + co) * p.CinP + k % 3);
+        const float b = p.bias ? p.bias[co] : 0.f;
+        if (k == 27) return kBf16 ? bf16_to_f32(f32_to_bf16(b)) : b;
+        if (k == 28 && kBf16) return b - bf16_to_f32(f32_to_bf16(b));
+        return 0.f;
+    };
+    // The whole filter bank, loaded once per workgroup and kept in registers.
     bf16x8 bfrag16[kBf16 ? 2 : 1][2];
     float bfrag32[kBf16 ? 1 : 14][2];
     if constexpr (kBf16) {
@@ -64,9 +76,6 @@ __global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
 #pragma unroll
             for (int j = 0; j < 2; ++j) bfrag32[s][j] = wval(2 * s + khalf, j * 32 + r);
     }
-    float bv[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) bv[j] = p.bias ? p.bias[j * 32 + r] : 0.f;
 
     // halo origin (float offset) of this lane's two pixels: tile rows wv*64 + i*32 + r
     int pbase[2];
@@ -79,20 +88,48 @@ __global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
     char *epi = epi_all + wv * kFirstEpiBytes;
     T *y = reinterpret_cast<T *>(p.y);
     const int seg = lane & 7, rowq = lane >> 3;
+    const float lo = p.relu ? 0.f : -__builtin_inff();
 
-    for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
-        const int n = tile / p.tiles_hw;
+    // The halo elements this thread stages: the same positions of every patch.
+    int hy_[kHaloPerThread], hx_[kHaloPerThread], lds_[kHaloPerThread], rel_[kHaloPerThread];
+#pragma unroll
+    for (int k = 0; k < kHaloPerThread; ++k) {
+        const int idx = min(tid + k * 256, kHaloElems - 1);
+        const int c = idx / 324, q = idx - c * 324, hy = q / 18, hx = q - hy * 18;
+        hy_[k] = hy - 1; hx_[k] = hx - 1;
+        lds_[k] = (c * 18 + hy) * kHaloW + hx;
+        rel_[k] = (c * p.H + hy - 1) * p.W + hx - 1;
+    }
+    auto load_halo = [&](int tile, float (&hv)[kHaloPerThread]) __attribute__((always_inline)) {
+        const int n = fast_div(tile, p.dTilesHW);
         const int rem = tile - n * p.tiles_hw;
-        const int h0 = (rem / p.tiles_w) * 16, w0 = (rem % p.tiles_w) * 16;
-        __syncthreads();  // previous tile's halo no longer read
-        for (int idx = tid; idx < 3 * 18 * 18; idx += 256) {
-            const int c = idx / 324, q = idx - c * 324, hy = q / 18, hx = q - hy * 18;
-            const int h = h0 - 1 + hy, w = w0 - 1 + hx;
-            float v = 0.f;
-            if (h >= 0 && h < p.H && w >= 0 && w < p.W) v = p.x[(((size_t)n * 3 + c) * p.H + h) * p.W + w];
-            xs[(c * 18 + hy) * kHaloW + hx] = v;
+        const int ty = fast_div(rem, p.dTilesW);
+        const int h0 = ty * 16, w0 = (rem - ty * p.tiles_w) * 16;
+        const float *base = p.x + (size_t)n * 3 * p.H * p.W + h0 * p.W + w0;
+#pragma unroll
+        for (int k = 0; k < kHaloPerThread; ++k) {
+            const int h = h0 + hy_[k], w = w0 + hx_[k];
+            const bool ok = h >= 0 && h < p.H && w >= 0 && w < p.W;
+            hv[k] = ok ? base[rel_[k]] : 0.f;
         }
+    };
+    auto store_halo = [&](const float (&hv)[kHaloPerThread]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kHaloPerThread; ++k)
+            if ((k + 1) * 256 <= kHaloElems || tid + k * 256 < kHaloElems) xs[lds_[k]] = hv[k];
+    };
+
+    float hv[kHaloPerThread];
+    if ((int)blockIdx.x < p.ntiles) load_halo(blockIdx.x, hv);
+    for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+        const int n = fast_div(tile, p.dTilesHW);
+        const int rem = tile - n * p.tiles_hw;
+        const int ty = fast_div(rem, p.dTilesW);
+        const int h0 = ty * 16, w0 = (rem - ty * p.tiles_w) * 16;
+        __syncthreads();  // previous tile's halo no longer read
+        store_halo(hv);
         __syncthreads();
+        if (tile + (int)gridDim.x < p.ntiles) load_halo(tile + gridDim.x, hv);  // lands during the arithmetic below
 
         f32x16 acc[2][2];
 #pragma unroll
@@ -109,16 +146,18 @@ __global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
                 bf16x8 afrag[2];
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
-                    const int k = s * 16 + khalf * 8 + t;
-                    const int off = khalf ? first_koff(s * 16 + 8 + t) : first_koff(s * 16 + t);
+                    const int k0 = s * 16 + t, k1 = s * 16 + 8 + t;       // this lane's k is k0 or k1
+                    const int off = khalf ? first_koff(k1) : first_koff(k0);
+                    const bool data = khalf ? k1 < 27 : k0 < 27;
+                    const float pad = (khalf ? (k1 == 27 || k1 == 28) : (k0 == 27 || k0 == 28)) ? 1.f : 0.f;
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) afrag[i][t] = (__bf16)(k < 27 ? xs[pbase[i] + off] : 0.f);
+                    for (int i = 0; i < 2; ++i) afrag[i][t] = (__bf16)(data ? xs[pbase[i] + off] : pad);
                 }
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[i], bfrag16[s][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag16[s][j], afrag[i], acc[i][j], 0, 0, 0);
             }
         } else {
             // fourteen steps of v_mfma_f32_32x32x2_f32: k = 2*s + khalf
@@ -128,16 +167,17 @@ __global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
                 const int off = khalf ? first_koff(2 * s + 1) : first_koff(2 * s);
                 float a[2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) a[i] = k < 27 ? xs[pbase[i] + off] : 0.f;
+                for (int i = 0; i < 2; ++i) a[i] = k < 27 ? xs[pbase[i] + off] : (k == 27 ? 1.f : 0.f);
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], bfrag32[s][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag32[s][j], a[i], acc[i][j], 0, 0, 0);
             }
         }
 
-        // epilogue: bias, ReLU, transpose 32 rows x 128 bytes through this wave's LDS block, 16-byte stores
+        // epilogue: register e of lane l is channel 8*(e/4) + 4*(l/32) + e%4 of pixel row l%32; ReLU,
+        // 32 pixels x 128 bytes through this wave's LDS block, 16-byte stores
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -145,11 +185,11 @@ __global__ __launch_bounds__(256) void conv_first_kernel(FirstArgs p)
 #pragma unroll
                 for (int jj = 0; jj < TJ; ++jj) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        float v = acc[i][j0 + jj][e] + bv[j0 + jj];
-                        if (p.relu) v = fmaxf(v, 0.f);
-                        const int row = (e >> 2) * 8 + khalf * 4 + (e & 3);
-                        Elem<T>::store(reinterpret_cast<T *>(epi + row * kFirstEpiRow) + jj * 32 + r, v);
+                    for (int a = 0; a < 4; ++a) {
+                        const f32x16 &t = acc[i][j0 + jj];
+                        store4(reinterpret_cast<T *>(epi + r * kFirstEpiRow) + jj * 32 + a * 8 + khalf * 4,
+                               fmaxf(t[a * 4], lo), fmaxf(t[a * 4 + 1], lo), fmaxf(t[a * 4 + 2], lo),
+                               fmaxf(t[a * 4 + 3], lo));
                     }
                 }
 #pragma unroll
@@ -176,6 +216,7 @@ int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const v
     a.tiles_w = (W + 15) / 16;
     a.tiles_hw = a.tiles_w * ((H + 15) / 16);
     a.ntiles = N * a.tiles_hw;
+    a.dTilesW = make_fast_div(a.tiles_w); a.dTilesHW = make_fast_div(a.tiles_hw);
     const dim3 grid((unsigned)(a.ntiles < 2048 ? a.ntiles : 2048));
     if (dtype == VGG_BF16)
         hipLaunchKernelGGL(conv_first_kernel<bf16_t>, grid, dim3(256), 0, stream, a);
