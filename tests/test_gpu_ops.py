@@ -22,6 +22,7 @@ CONV_SHAPES = [
     (1, 2, 2, 16, 64),
     (5, 16, 48, 32, 192),
     (1, 56, 56, 64, 64),
+    (1, 6, 100, 16, 32),   # wide rows: halo beyond the direct-to-LDS kernels' limit, weight-gradient halo in several batches
 ]
 
 
