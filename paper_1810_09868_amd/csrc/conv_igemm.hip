@@ -380,9 +380,10 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
 }
 
 // ---------------------------------------------------------------------------
-// Variant with direct-to-LDS weight loads.  LDS rows are 64 bytes without
-// padding; the 16-byte segment s of row q lives at segment s ^ ((q >> 2) & 3),
-// which keeps the fragment reads of 16 consecutive rows on distinct banks.
+// Variant with direct-to-LDS weight loads.  Weight rows in LDS are 64 bytes
+// without padding; the 16-byte segment s of row q lives at segment
+// s ^ ((q >> 2) & 3), which keeps the fragment reads of 16 consecutive rows on
+// distinct banks (halo rows likewise, or padded to 80 bytes where LDS allows).
 // The weights of a stage are copied by global_load_lds_dwordx4 (lane l of a
 // wave writes bytes [16 l, 16 l + 16) of a 1 KB block, so each lane fetches the
 // segment that belongs at its position) into one of two buffers while the
@@ -403,6 +404,11 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     constexpr int SEGS = SA * 4;                    // 16-byte halo segments per chunk
     constexpr int MAXA = (SEGS + NT - 1) / NT;      // of which each thread copies at most MAXA
     constexpr int b_bytes = 3 * BN * kDataBytes;
+    // Halo rows of the 8-wave kernel with the smaller halo are padded to 80 bytes instead of swizzled:
+    // conflict-free as well, and linear, so every tap of a fragment read is the same per-lane
+    // address plus an immediate offset (the other variants have no LDS left for the padding).
+    constexpr bool APAD = SA == kDmaHaloRows && NW == 8;
+    constexpr int AROW = APAD ? kRowBytes : kDataBytes;
     constexpr int NB = 3 * BN / 16 / NW;            // 1 KB blocks of a weight stage per wave
     static_assert(3 * BN % (16 * NW) == 0 && BN % 16 == 0, "weight stage must split into whole 1 KB blocks");
 
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     const int S = p.g.S;
     int *pix = reinterpret_cast<int *>(smem);       // [SA]
     char *As = smem + SA * 4;                        // [SA][64]
-    char *Bs = As + SA * kDataBytes;                 // [2][3*BN][64]
+    char *Bs = As + SA * AROW;                       // [2][3*BN][64]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -427,38 +433,45 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     const TileOrigin org = tile_origin(p.g, tile_m);
     const int pitch = p.g.pitch;
 
-    // this lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes
+    // This lane's part of the weight stage (c0, kh): NB blocks of 16 rows x 64 bytes.  The per-lane
+    // byte offsets inside a kernel row's weights never change; the stage only moves a scalar base.
+    unsigned woff[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+        const int row = (wv * NB + q) * 16 + (lane >> 2);   // kw*BN + n
+        const int kw = row / BN;
+        const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
+        woff[q] = (unsigned)((kw * p.Cout + n) * p.CinP) * (unsigned)sizeof(T) + ((((lane & 3) ^ swz(row))) << 4);
+    }
+    const unsigned bs_lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + wv * NB * 1024));
     auto dma_b = [&](int c0, int kh, int buf) __attribute__((always_inline)) {
+        const char *base = p.w + ((size_t)(kh * 3) * p.Cout * p.CinP + c0) * sizeof(T);
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
-            const int blk = wv * NB + q;
-            const int row = blk * 16 + (lane >> 2);          // kw*BN + n
-            const int kw = row / BN;
-            const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
-            const int seg = (lane & 3) ^ swz(row);
-            const char *src = p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + seg * 16;
             // Issued as inline assembly on purpose: the compiler cannot tell that this write and the
             // fragment reads of the other buffer never overlap and would wait for it before every read.
-            const unsigned dst = __builtin_amdgcn_readfirstlane(
-                (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + buf * b_bytes + blk * 1024));
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "m0", "memory");
+            const unsigned dst = bs_lds + buf * b_bytes + q * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(woff[q]), "s"(base) : "m0", "memory");
         }
     };
     dma_b(0, 0, 0);  // first: its latency covers the index arithmetic below
 
     for (int i = tid; i < SA; i += NT) pix[i] = i < S ? halo_pixel(p.g, org, i) : -1;
 
-    int arow[TM];
+    int arow[TM];   // halo row of tap (0,0) of this lane's pixels; padded layout: its byte address
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         int m;
         tile_row(p.g, org, wm * (BM / WM) + i * 32 + r, m, arow[i]);
+        if (APAD) arow[i] = arow[i] * AROW + khalf * 16;
     }
-    int baddr[TN];  // k-group 0; k-group 1 is at ^32; tap kw adds kw*BN*64
+    int baddr[2][TN];  // per k-group; tap kw adds kw*BN*64
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int row = wn * (BN / WN) + j * 32 + r;
-        baddr[j] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+        baddr[0][j] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+        baddr[1][j] = baddr[0][j] ^ 32;
     }
 
     f32x16 acc[TM][TN];
@@ -484,26 +497,35 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
             const int idx = tid + j * NT;
             const int row = idx >> 2;
             if ((j + 1) * NT <= SEGS || idx < SEGS)
-                *reinterpret_cast<u32x4 *>(As + row * kDataBytes + (((idx & 3) ^ swz(row)) << 4)) = areg[j];
+                *reinterpret_cast<u32x4 *>(As + row * AROW + (APAD ? (idx & 3) << 4 : ((idx & 3) ^ swz(row)) << 4)) = areg[j];
         }
     };
     auto compute = [&](int kh, const char *Bt) __attribute__((always_inline)) {
+        const char *arow_kh[TM];  // padded layout: this stage's kernel row, once per stage
+        if (APAD) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) arow_kh[i] = As + arow[i] + kh * pitch * AROW;
+        }
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
             int aaddr[TM];
+            if (!APAD) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = arow[i] + kh * pitch + kw;
-                aaddr[i] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+                for (int i = 0; i < TM; ++i) {
+                    const int row = arow[i] + kh * pitch + kw;
+                    aaddr[i] = row * kDataBytes + ((khalf ^ swz(row)) << 4);
+                }
             }
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 uint4 af[TM], bf[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const uint4 *>(As + (aaddr[i] ^ (g * 32)));
+                for (int i = 0; i < TM; ++i)
+                    af[i] = APAD ? *reinterpret_cast<const uint4 *>(arow_kh[i] + kw * AROW + g * 32)
+                                 : *reinterpret_cast<const uint4 *>(As + (aaddr[i] ^ (g * 32)));
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    bf[j] = *reinterpret_cast<const uint4 *>(Bt + kw * BN * kDataBytes + (baddr[j] ^ (g * 32)));
+                    bf[j] = *reinterpret_cast<const uint4 *>(Bt + kw * BN * kDataBytes + baddr[g][j]);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -550,7 +572,8 @@ static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t st
     a.g = g;
     a.tiles_n = (a.Cout + BN - 1) / BN;
     a.rowsA = SA;
-    size_t lds = (size_t)a.rowsA * 4 + (size_t)a.rowsA * kDataBytes + (size_t)2 * 3 * BN * kDataBytes;
+    const size_t arow_bytes = (SA == kDmaHaloRows && WM * WN == 8) ? kRowBytes : kDataBytes;   // as in the kernel
+    size_t lds = (size_t)a.rowsA * 4 + (size_t)a.rowsA * arow_bytes + (size_t)2 * 3 * BN * kDataBytes;
     if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
     auto kern = conv3x3_igemm_dma_kernel<T, BM, BN, WM, WN, SA>;
     static bool configured = false;
