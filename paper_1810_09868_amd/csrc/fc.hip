@@ -81,10 +81,13 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
-    for (int u0 = u_begin; u0 < u_end; u0 += 4) {
+    // Both operands of a step are requested one step ahead and held in registers, so the weight
+    // stream from HBM never pauses for the staging and the MFMAs.  The barriers are issued without
+    // the fence of __syncthreads(), which would wait for those loads.
+    auto barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    constexpr int NA = 4 * 128 * 4 / 256;   // activation segments per thread and step
+    auto load_w = [&](int u0, uint4 (&bf)[4][2]) __attribute__((always_inline)) {
         const int nu = min(4, u_end - u0);
-        // weight fragments for this step: nu units x 2 k-groups
-        uint4 bf[4][2];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -93,15 +96,34 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
                 if (u < nu && ook)
                     bf[u][g] = *reinterpret_cast<const uint4 *>(wrow + (size_t)(u0 + u) * 64 + g * 32);
             }
-        __syncthreads();
-        for (int idx = tid; idx < 4 * 128 * 4; idx += 256) {
+    };
+    auto load_a = [&](int u0, uint4 (&av)[NA]) __attribute__((always_inline)) {
+        const int nu = min(4, u_end - u0);
+#pragma unroll
+        for (int k = 0; k < NA; ++k) {
+            const int idx = tid + k * 256;
             const int seg = idx & 3, row = (idx >> 2) & 127, u = idx >> 9;
-            uint4 v = make_uint4(0, 0, 0, 0);
+            av[k] = make_uint4(0, 0, 0, 0);
             if (u < nu && row0 + row < p.N)
-                v = *reinterpret_cast<const uint4 *>(p.a + (size_t)(row0 + row) * rowbytes + (size_t)(u0 + u) * 64 + seg * 16);
-            *reinterpret_cast<uint4 *>(As + (u * 128 + row) * kFcRow + seg * 16) = v;
+                av[k] = *reinterpret_cast<const uint4 *>(p.a + (size_t)(row0 + row) * rowbytes + (size_t)(u0 + u) * 64 + seg * 16);
         }
-        __syncthreads();
+    };
+    uint4 bf_next[4][2], a_next[NA];
+    if (u_begin < u_end) { load_a(u_begin, a_next); load_w(u_begin, bf_next); }
+    for (int u0 = u_begin; u0 < u_end; u0 += 4) {
+        barrier();  // the previous step's fragment reads are done
+#pragma unroll
+        for (int k = 0; k < NA; ++k) {
+            const int idx = tid + k * 256;
+            *reinterpret_cast<uint4 *>(As + ((idx >> 9) * 128 + ((idx >> 2) & 127)) * kFcRow + (idx & 3) * 16) = a_next[k];
+        }
+        uint4 bf[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) bf[u][g] = bf_next[u][g];
+        if (u0 + 4 < u_end) { load_a(u0 + 4, a_next); load_w(u0 + 4, bf_next); }
+        barrier();  // the staged activations are visible
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
