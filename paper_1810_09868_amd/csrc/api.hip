@@ -11,7 +11,7 @@ bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
-int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
+int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
                   hipStream_t stream);
 int maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *arg, hipStream_t s);
 int maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy, const uint8_t *arg, void *dx, hipStream_t s);
@@ -262,7 +262,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             cur ^= 1;
         }
         const char *xin = l == 0 ? ws + L.x0 : (pool_after(l - 1) ? ws + L.pooled[l - 1] : ws + L.act[l - 1]);
-        VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, P.cinp[l], Cout, reinterpret_cast<const float *>(xin), F(gbuf[cur]),
+        VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin), F(gbuf[cur]),
                                             F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
         if (l > 0) {
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
@@ -486,7 +486,7 @@ int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, co
         x = wsp;
         wsp += round_up((size_t)N * H * W * cp * 4, 256);
     }
-    return conv3x3_wgrad(N, H, W, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp, s);
+    return conv3x3_wgrad(N, H, W, Cin, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp, s);
 }
 
 int vgg_maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *argmax, void *stream)

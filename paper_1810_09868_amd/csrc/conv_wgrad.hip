@@ -247,25 +247,193 @@ __global__ __launch_bounds__(kWaves * 64, 4) void conv3x3_wgrad_kernel(WgradArgs
     else wgrad_body<5, 4, kPK / 8>(p, smem);
 }
 
-__global__ void wgrad_reduce_kernel(const float *part, float *out, size_t n, int splits)
+// Layers with at most three input channels (the first one): (tap, ci) pairs are the <= 27 columns
+// of a single 32-wide MFMA tile, so a pair of pixels costs one MFMA per 32 output channels instead
+// of nine.  Column c = tap*CI + ci of pixel m is x[m + tap][ci]: lane c reads it from the staged halo
+// at a lane-constant offset.  Staging as in the general kernel.  Eight waves = (co half) x (pixel
+// quarter); the quarters are added through LDS at the end.
+__global__ __launch_bounds__(kWaves * 64, 4) void conv3x3_wgrad_thin_kernel(WgradArgs p, int CI)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += part[(size_t)k * n + i];
-    out[i] = s;
+    extern __shared__ __align__(16) char smem[];
+    const int buf_bytes = kPK * kGRow + p.SX * kXRow;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, kp = lane >> 5;
+    const int wc = wv & 1, wp = wv >> 1;  // co half, pixel quarter
+
+    int b = blockIdx.x;
+    const int tco = b % p.tiles_co; b /= p.tiles_co;
+    const int split = b;
+    const int co0 = tco * kBCO;
+    const int pitch = p.geo.pitch;
+
+    // this lane's column: tap and channel, as a byte offset from the halo row of tap (0,0)
+    const bool cvalid = r < 9 * CI;
+    const int tap = cvalid ? r / CI : 0, ci = cvalid ? r - tap * CI : 0;
+    const int coff = ((tap / 3) * pitch + tap % 3) * kXRow + ci * 4;
+
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    float gsum = 0.f;
+
+    const int t_begin = split * p.tiles_per_split;
+    const int t_end = min(t_begin + p.tiles_per_split, p.geo.ntiles);
+
+    constexpr int kGOps = kPK / 4 / kWaves;
+    const int nxw = ((p.SX >> 3) - wv + kWaves - 1) / kWaves;
+    const int gsub = lane >> 4;
+    const int gcol = co0 + (((lane & 15) ^ ((gsub & 1) << 3)) << 2);
+    const bool gok = gcol < p.Cout;
+    const int xsub = lane >> 3;
+    const int xcol = (lane & 7) << 2;
+    const bool xok = xcol < p.CinP;
+    const float *zero = reinterpret_cast<const float *>(kZeroSeg);
+    auto dma = [&](const float *src, char *dst) __attribute__((always_inline)) {
+        const unsigned d = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)dst);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(d), "v"(src) : "m0", "memory");
+    };
+    // all copies of a tile, in one go (there is little arithmetic to hide them behind)
+    auto issue_tile = [&](const TileOrigin &org, char *base, int m_l) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kGOps; ++k) {
+            const int q = wv + kWaves * k;
+            const int m = __builtin_amdgcn_ds_bpermute((q * 4 + gsub) << 2, m_l);
+            dma((gok && m >= 0) ? p.g + (size_t)m * p.Cout + gcol : zero, base + q * 1024);
+        }
+        for (int k0 = 0; k0 < nxw; k0 += 8) {
+            const int kk = k0 + (lane >> 3);
+            const int i = (wv + kWaves * kk) * 8 + (lane & 7);
+            const int px_l = (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
+            const int kn = min(nxw - k0, 8);
+            for (int k = 0; k < kn; ++k) {
+                const int px = __builtin_amdgcn_ds_bpermute(((k << 3) + xsub) << 2, px_l);
+                dma((xok && px >= 0) ? p.x + (size_t)px * p.CinP + xcol : zero,
+                    base + kPK * kGRow + (wv + kWaves * (k0 + k)) * 1024);
+            }
+        }
+    };
+
+    const int wrow0 = __builtin_amdgcn_readfirstlane(wp * (kPK / 4));
+    int hrow_l = 0;
+    if (t_begin < t_end) {
+        const TileOrigin org0 = tile_origin(p.geo, t_begin);
+        int m_l;
+        tile_row(p.geo, org0, lane, m_l, hrow_l);
+        issue_tile(org0, smem, m_l);
+    }
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const int buf = (tile - t_begin) & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this tile's copies have landed
+        __syncthreads();
+        int hrow_next = 0;
+        if (tile + 1 < t_end) {
+            const TileOrigin orgn = tile_origin(p.geo, tile + 1);
+            int m_l;
+            tile_row(p.geo, orgn, lane, m_l, hrow_next);
+            issue_tile(orgn, smem + (buf ^ 1) * buf_bytes, m_l);
+        }
+        const char *Gs = smem + buf * buf_bytes;
+        const char *Xs = Gs + kPK * kGRow + coff;
+        const char *ga = Gs + (wrow0 + kp) * kGRow + (((wc * 32 + r) ^ (kp << 5)) << 2);
+        // this wave: pixels [wp*16, wp*16+16) of the tile, two per MFMA
+#pragma unroll
+        for (int s = 0; s < kPK / 8; ++s) {
+            const int h0 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s);
+            const int h1 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s + 1);
+            const float a = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
+            const float bv = *reinterpret_cast<const float *>(Xs + (kp ? h1 : h0) * kXRow);
+            gsum += a;
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc, 0, 0, 0);
+        }
+        hrow_l = hrow_next;
+    }
+
+    // add the four pixel quarters: waves with wp > 0 park their sums in LDS
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem);            // [2][3][16][64]
+    float *dbs = red + 2 * 3 * 16 * 64;                      // [2][3][32]
+    gsum += __shfl_xor(gsum, 32, kWave);                     // the other pixel of the pair
+    if (wp > 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[((wc * 3 + wp - 1) * 16 + e) * 64 + lane] = acc[e];
+        if (kp == 0) dbs[(wc * 3 + wp - 1) * 32 + r] = gsum;
+    }
+    __syncthreads();
+    if (wp == 0) {
+        // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (co), column l%32 (tap, ci)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int co = co0 + wc * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+            float v = acc[e];
+#pragma unroll
+            for (int q = 0; q < 3; ++q) v += red[((wc * 3 + q) * 16 + e) * 64 + lane];
+            if (cvalid && co < p.Cout) p.part[(((size_t)split * 9 + tap) * p.Cout + co) * p.CinP + ci] = v;
+        }
+        if (p.dbpart && kp == 0) {
+            const int co = co0 + wc * 32 + r;
+            float v = gsum;
+#pragma unroll
+            for (int q = 0; q < 3; ++q) v += dbs[(wc * 3 + q) * 32 + r];
+            if (co < p.Cout) p.dbpart[(size_t)split * p.Cout + co] = v;
+        }
+    }
+    // padding channels of this block's partial sums: exact zeros
+    for (int i = tid; i < 9 * kBCO * (p.CinP - CI); i += kWaves * 64) {
+        const int cpad = p.CinP - CI;
+        const int t = i / (kBCO * cpad), rem = i - t * (kBCO * cpad), col = rem / cpad, c = CI + rem - col * cpad;
+        if (co0 + col < p.Cout) p.part[(((size_t)split * 9 + t) * p.Cout + co0 + col) * p.CinP + c] = 0.f;
+    }
 }
 
-static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a)
+// out[i] = sum over the splits of part[k][i], in a fixed order.  A workgroup owns 256/RY outputs;
+// thread row y adds the splits k = y, y + RY, ... and the RY rows are then added through LDS, so
+// that launches with few outputs and many splits (bias gradients, thin layers) still fill the chip.
+template <int RY>
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *part, float *out, size_t n, int splits)
+{
+    constexpr int RX = 256 / RY;
+    __shared__ float red[256];
+    const int x = threadIdx.x % RX, y = threadIdx.x / RX;
+    const size_t i = (size_t)blockIdx.x * RX + x;
+    float s = 0.f;
+    if (i < n)
+        for (int k = y; k < splits; k += RY) s += part[(size_t)k * n + i];
+    if (RY == 1) {
+        if (i < n) out[i] = s;
+        return;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (y == 0 && i < n) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < RY; ++r) t += red[r * RX + x];
+        out[i] = t;
+    }
+}
+
+static void launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream)
+{
+    if (splits >= 128)
+        hipLaunchKernelGGL(wgrad_reduce_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, part, out, n, splits);
+    else if (splits >= 16)
+        hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, stream, part, out, n, splits);
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, part, out, n, splits);
+}
+
+static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a, bool thin = false)
 {
     a.geo = make_tile_geom(N, H, W, kPK);
     a.SX = (a.geo.S + 7) & ~7;
     if (a.SX < 8 * kWaves) a.SX = 8 * kWaves;  // every wave copies at least one halo block
     a.CinP = CinP; a.Cout = Cout;
     a.tiles_co = (Cout + kBCO - 1) / kBCO;
-    a.tiles_ci = (CinP + kBCI - 1) / kBCI;
+    a.tiles_ci = thin ? 1 : (CinP + kBCI - 1) / kBCI;
     const int groups = a.tiles_co * a.tiles_ci;
-    int splits = (2048 + groups - 1) / groups;
+    // (thin kernel: little arithmetic per tile, and its few outputs are summed over the splits by few
+    // threads, so one resident round of workgroups)
+    int splits = ((thin ? 512 : 2048) + groups - 1) / groups;
     if (splits > a.geo.ntiles) splits = a.geo.ntiles;
     if (splits < 1) splits = 1;
     a.tiles_per_split = (a.geo.ntiles + splits - 1) / splits;
@@ -279,12 +447,13 @@ size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout)
     return round_up((size_t)a.splits * 9 * Cout * CinP * 4, 256) + round_up((size_t)a.splits * Cout * 4, 256);
 }
 
-// x [M][CinP] fp32, g [M][Cout] fp32 -> dw [9][Cout][CinP], db [Cout] (may be null).
-int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const float *g, float *dw,
+// x [M][CinP] fp32 (channels >= Cin are zero), g [M][Cout] fp32 -> dw [9][Cout][CinP], db [Cout] (may be null).
+int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw,
                   float *db, void *ws, hipStream_t stream)
 {
+    const bool thin = Cin <= 3 && CinP <= kBCI;
     WgradArgs a;
-    wgrad_plan(N, H, W, CinP, Cout, a);
+    wgrad_plan(N, H, W, CinP, Cout, a, thin);
     a.x = x; a.g = g;
     const size_t nw = (size_t)9 * Cout * CinP;
     a.part = static_cast<float *>(ws);
@@ -297,18 +466,20 @@ int conv3x3_wgrad(int N, int H, int W, int CinP, int Cout, const float *x, const
     static bool configured = false;
     if (lds > 64 * 1024 && !configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_thin_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return VGG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3((unsigned)(a.tiles_co * a.tiles_ci * a.splits)), dim3(kWaves * 64), lds,
-                       stream, a);
+    const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
+    if (thin)
+        hipLaunchKernelGGL(conv3x3_wgrad_thin_kernel, grid, dim3(kWaves * 64), lds, stream, a, Cin);
+    else
+        hipLaunchKernelGGL(conv3x3_wgrad_kernel, grid, dim3(kWaves * 64), lds, stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, stream, a.part, dw, nw,
-                       a.splits);
-    if (db)
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((Cout + 255) / 256)), dim3(256), 0, stream, a.dbpart,
-                           db, (size_t)Cout, a.splits);
+    launch_reduce(a.part, dw, nw, a.splits, stream);
+    if (db) launch_reduce(a.dbpart, db, (size_t)Cout, a.splits, stream);
     return launch_status();
 }
 
