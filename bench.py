@@ -153,6 +153,54 @@ def run_train_bench(N, steps, inp_seed=0):
             "pct_fp32_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS["f32"], "ms_by_kind": by_kind}
 
 
+def batch_sweep(dtype_name, batches, steps):
+    """Forward pass at the other batch sizes of the paper's timing table (1 and 10 images): ms and images/s."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd import synth
+    from paper_1810_09868_amd.model import Vgg19
+    dtype = B.BF16 if dtype_name == "bf16" else B.F32
+    res = []
+    for N in batches:
+        inp = synth.full_config(N, seed=0, with_labels=False)
+        m = Vgg19(dtype, N, 224, 224, 4096, 1000)
+        m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+        x = torch.from_numpy(inp.x).cuda()
+        for _ in range(3):
+            m.forward(x)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            m.forward(x)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        res.append({"batch": N, "ms_per_step": round(dt * 1e3, 4), "images_per_s": round(N / dt, 1)})
+        del m
+        torch.cuda.empty_cache()
+    return res
+
+
+def mfma_loop_ceiling():
+    """TFLOP/s of a loop of nothing but MFMAs (register operands), constant and random operands: what the chip
+    sustains at the clock it holds under matrix load, next to the data-sheet peak used for `roofline.peak`."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    sink = torch.empty((B.vgg_mfma_probe_sink_bytes(),), dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, dt, iters in (("bf16", B.BF16, 20000), ("f32", B.F32, 10000)):   # about 10 ms per launch
+        for rnd in (False, True):
+            B.vgg_mfma_probe(dt, rnd, iters // 2, sink)   # warm-up: the clock settles under load
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = B.vgg_mfma_probe(dt, rnd, iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            out["%s_%s_operands_tflops" % (name, "random" if rnd else "constant")] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return out
+
+
 def cpu_baseline(inp, images):
     from oracle import vgg_ref as R
     t0 = time.perf_counter()
@@ -228,6 +276,8 @@ def main():
                             "roofline": sec["roofline"]}
     if not a.no_secondary:
         out["train_step"] = run_train_bench(a.batch, max(2, a.steps // 5))
+        out["batch_sweep"] = batch_sweep(a.dtype, (1, 10), max(5, a.steps))
+    out["mfma_loop_ceiling"] = mfma_loop_ceiling()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, min(a.cpu_images, a.batch))
     print(json.dumps(out))

@@ -267,6 +267,21 @@ int vgg19_timed(const vgg_config *cfg, int training, const float *x_nchw, const 
                 void *packed, size_t packed_bytes, float *logits, void *ws, size_t ws_bytes,
                 int *kinds_host, float *ms_host, int cap, void *stream);
 
+/* Measurement aid, not a step of the path: a loop of nothing but MFMA
+ * instructions (register operands, 2x2 accumulator blocks, four waves per
+ * SIMD on every CU), bf16 (v_mfma_f32_32x32x16_bf16) or fp32
+ * (v_mfma_f32_32x32x2_f32), with all operands 1.0 (random_operands == 0) or
+ * with random mantissas and signs.  Timing it gives the matrix rate this chip
+ * sustains at the clock it holds under that load, against which the
+ * convolution kernels' rate can be read next to the data-sheet peak.
+ * sink: device buffer of vgg_mfma_probe_sink_bytes() bytes (results are
+ * written there so that the loop is not optimised away); *flops_host (host,
+ * may be null) receives the number of floating-point operations of the launch.
+ * Asynchronous on `stream`; iters > 0 else VGG_ERR_SHAPE. */
+size_t vgg_mfma_probe_sink_bytes(void);
+int vgg_mfma_probe(int dtype, int random_operands, int iters, float *sink, size_t sink_bytes,
+                   double *flops_host, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

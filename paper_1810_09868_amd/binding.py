@@ -28,7 +28,7 @@ EXPORTS = [
     "vgg_softmax", "vgg_softmax_xent_bwd", "vgg_sgd_update",
     "vgg19_packed_bytes", "vgg19_forward_workspace_bytes", "vgg19_train_workspace_bytes",
     "vgg19_pack_params", "vgg19_unpack_params", "vgg19_forward", "vgg19_train_step", "vgg19_plan",
-    "vgg19_timed",
+    "vgg19_timed", "vgg_mfma_probe_sink_bytes", "vgg_mfma_probe",
 ]
 
 
@@ -101,6 +101,9 @@ def lib() -> C.CDLL:
         L.vgg19_plan.argtypes = [cfgp, _i, C.POINTER(C.c_int), _i]
         L.vgg19_timed.argtypes = [cfgp, _i, _vp, _vp, _vp, _sz, _vp, _vp, _sz, C.POINTER(C.c_int),
                                   C.POINTER(C.c_float), _i, _vp]
+        L.vgg_mfma_probe_sink_bytes.restype = _sz
+        L.vgg_mfma_probe_sink_bytes.argtypes = []
+        L.vgg_mfma_probe.argtypes = [_i, _i, _i, _vp, _sz, C.POINTER(C.c_double), _vp]
         _LIB = L
     return _LIB
 
@@ -295,3 +298,15 @@ def vgg19_timed(cfg, training: bool, x_nchw, labels, packed, logits, ws):
     if rc < 0:
         raise VggError(rc, "vgg19_timed")
     return list(kinds), list(ms)
+
+
+def vgg_mfma_probe_sink_bytes() -> int:
+    return lib().vgg_mfma_probe_sink_bytes()
+
+
+def vgg_mfma_probe(dtype, random_operands: bool, iters: int, sink) -> float:
+    """Enqueues the MFMA-only loop; returns the number of floating-point operations it performs."""
+    flops = C.c_double(0.0)
+    _chk(lib().vgg_mfma_probe(dtype, int(random_operands), iters, _ptr(sink), _nbytes(sink), C.byref(flops), _stream()),
+         "vgg_mfma_probe")
+    return flops.value

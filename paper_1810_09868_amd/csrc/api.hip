@@ -13,6 +13,8 @@ int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const v
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
 int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
                   hipStream_t stream);
+size_t mfma_probe_sink_bytes();
+int mfma_probe(int dtype, int random, int iters, float *sink, double *flops, hipStream_t stream);
 int maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *arg, hipStream_t s);
 int maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy, const uint8_t *arg, void *dx, hipStream_t s);
 int softmax_rows(int N, int K, const float *z, float *p, hipStream_t s);
@@ -123,12 +125,17 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         }
     } else {
         const size_t pA = b.take(max_act), pB = b.take(max_act);
-        // forward ping-pong: every op reads one buffer and writes the other
+        // forward ping-pong: every launch reads one buffer and writes the other.  A convolution with
+        // the pool fused into its epilogue (see run_forward) writes only the pooled tensor, so that one
+        // takes the place of the convolution's output; it must never share the buffer of the input,
+        // which other workgroups of the same launch are still reading.
         int cur = 0;
         for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            const bool fuse = l > 0 && pool_after(l) && conv3x3_pool_fusable(c->dtype, L.H[l], L.W[l], kConvCh[l][1]);
             L.act[l] = cur ? pB : pA; cur ^= 1;
             L.pooled[l] = L.argmax[l] = 0;
-            if (pool_after(l)) { L.pooled[l] = cur ? pB : pA; cur ^= 1; }
+            if (fuse) L.pooled[l] = L.act[l];
+            else if (pool_after(l)) { L.pooled[l] = cur ? pB : pA; cur ^= 1; }
         }
     }
     L.z1 = b.take(N * c->fc_hidden * es);
@@ -726,6 +733,19 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap)
     else
         run_forward(cfg, P, L, nullptr, nullptr, nullptr, nullptr, true, nullptr, false, nullptr, rec);
     return rec.n;
+}
+
+size_t vgg_mfma_probe_sink_bytes(void) { return mfma_probe_sink_bytes(); }
+
+int vgg_mfma_probe(int dtype, int random_operands, int iters, float *sink, size_t sink_bytes, double *flops_host,
+                   void *stream)
+{
+    if (!sink) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (iters <= 0) return VGG_ERR_SHAPE;
+    if (!aligned16(sink)) return VGG_ERR_ALIGN;
+    if (sink_bytes < mfma_probe_sink_bytes()) return VGG_ERR_WORKSPACE;
+    return mfma_probe(dtype, random_operands != 0, iters, sink, flops_host, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -139,7 +139,27 @@ def test_full_vgg19_forward_batch100_sampled_images(dtype):
     probs = m.probs.cpu().numpy()
     assert np.isfinite(logits).all()
     np.testing.assert_allclose(probs.sum(1), 1.0, atol=1e-4)
-    for n in (0, 99):
+    # images from every part of the batch: a launch's workgroups run out of order across the chip, so a
+    # buffer that is read and written by the same launch would corrupt some images and not others
+    for n in (0, 1, 5, 13, 24, 38, 57, 76, 99):
+        ref = R.vgg19_forward(inp.x[n:n + 1], inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+        assert max_rel_err(logits[n:n + 1], ref["logits"]) <= TOL[dtype], n
+        _check_probs(probs[n:n + 1], logits[n:n + 1], ref, dtype)
+
+
+@pytest.mark.parametrize("N", [1, 10])
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_full_vgg19_forward_small_batches(dtype, N):
+    # the other batch sizes of the paper's timing table (Table "timing": 1, 10 and 100 images): the last
+    # stages then have fewer pixels than one workgroup tile per CU
+    inp = synth.full_config(N, seed=3, with_labels=False)
+    m = Vgg19(dtype, N, 224, 224, 4096, 1000)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    m.forward(dev(inp.x))
+    torch.cuda.synchronize()
+    logits = m.logits.cpu().numpy()
+    probs = m.probs.cpu().numpy()
+    for n in sorted({0, N // 3, N - 1}):
         ref = R.vgg19_forward(inp.x[n:n + 1], inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
         assert max_rel_err(logits[n:n + 1], ref["logits"]) <= TOL[dtype], n
         _check_probs(probs[n:n + 1], logits[n:n + 1], ref, dtype)

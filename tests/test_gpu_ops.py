@@ -276,3 +276,19 @@ def test_layout_roundtrip_and_convert():
     o2 = torch.empty((2,), dtype=torch.bfloat16, device="cuda")
     B.vgg_convert(B.F32, B.BF16, 2, halfway, o2)
     assert o2.float().tolist() == [1.0, 1.015625]                     # ties go to the even mantissa
+
+
+def test_mfma_probe_runs_and_reports_flops():
+    sink = torch.empty((B.vgg_mfma_probe_sink_bytes(),), dtype=torch.uint8, device="cuda")
+    for dt, per in ((B.BF16, 2 * 32 * 32 * 16), (B.F32, 2 * 32 * 32 * 2)):
+        flops = B.vgg_mfma_probe(dt, True, 10, sink)
+        torch.cuda.synchronize()
+        assert flops > 0 and flops % (10 * 8 * per) == 0
+    # constant operands: every accumulator element is the contraction length times the MFMA count
+    B.vgg_mfma_probe(B.BF16, False, 3, sink)
+    torch.cuda.synchronize()
+    vals = sink.view(torch.float32)[:256]
+    assert torch.all(vals == 4 * 16 * (3 * 8 // 4) * 16.0)
+    small = torch.empty((16,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.VggError):
+        B.vgg_mfma_probe(B.BF16, False, 3, small)
