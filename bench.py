@@ -137,6 +137,15 @@ def run_train_bench(N, steps, inp_seed=0):
         m.train_step(x, lab)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
+    # the same steps as one HIP graph: the training loop replayed by a single launch
+    g = m.capture_train_steps(x, lab, steps)
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.replay()
+    torch.cuda.synchronize()
+    dt_graph = (time.perf_counter() - t0) / steps
+    del g
     kinds, ms = B.vgg19_timed(m.cfg, True, x, lab, m.packed, m.logits, m.ws)
     names = {1: "conv_fwd", 2: "conv_dgrad", 3: "conv_wgrad", 4: "pool", 5: "pool_bwd", 6: "fc", 7: "fc_bwd", 9: "other"}
     by_kind = {}
@@ -150,7 +159,39 @@ def run_train_bench(N, steps, inp_seed=0):
     torch.cuda.empty_cache()
     return {"workload": "configs[4]: fp32 training step, batch %d, 3x224x224 (forward, mean cross-entropy, backward, SGD lr 0.01)" % N,
             "dtype": "f32", "ms_per_step": dt * 1e3, "images_per_s": N / dt, "tflops": flops / dt / 1e12,
-            "pct_fp32_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS["f32"], "ms_by_kind": by_kind}
+            "pct_fp32_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS["f32"], "ms_by_kind": by_kind,
+            "as_one_graph": {"steps_per_graph": steps, "ms_per_step": dt_graph * 1e3},
+            "tiny_config_loop": tiny_loop_bench()}
+
+
+def tiny_loop_bench(K=50):
+    """configs[0] (batch 2, 32x32) training loop, where launches rather than arithmetic set the pace: K eager
+    steps against K steps recorded into one HIP graph."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd import synth
+    from paper_1810_09868_amd.model import Vgg19
+    cfg = synth.tiny_config(seed=0)
+    m = Vgg19(B.F32, 2, 32, 32, 512, 10, lr=0.01, training=True)
+    m.pack(cfg.conv_w, cfg.conv_b, cfg.fc_w, cfg.fc_b)
+    x = torch.from_numpy(cfg.x).cuda()
+    lab = torch.from_numpy(cfg.labels).cuda()
+    for _ in range(3):
+        m.train_step(x, lab)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        m.train_step(x, lab)
+    torch.cuda.synchronize()
+    eager = (time.perf_counter() - t0) / K
+    g = m.capture_train_steps(x, lab, K)
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.replay()
+    torch.cuda.synchronize()
+    graph = (time.perf_counter() - t0) / K
+    return {"steps": K, "eager_ms_per_step": round(eager * 1e3, 4), "graph_ms_per_step": round(graph * 1e3, 4)}
 
 
 def batch_sweep(dtype_name, batches, steps):

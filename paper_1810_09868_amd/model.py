@@ -68,3 +68,19 @@ class Vgg19:
         B.vgg19_train_step(self.cfg, x, labels, self.packed, B.make_params(**g) if g else None, self.loss,
                            self.logits, self.ws)
         return g
+
+    def capture_train_steps(self, x: torch.Tensor, labels: torch.Tensor, steps: int) -> "torch.cuda.CUDAGraph":
+        """Records `steps` consecutive training steps on the given batch into one HIP graph, so that the whole
+        loop (forward, backward and update, `steps` times) is replayed by a single launch without returning to
+        the host in between: the training loop itself runs on the device, as in the paper's whole-program
+        compilation of "forward pass, backward pass and training loop" (introduction).  Call train_step once
+        before capturing (first use of a kernel sets its LDS limit, which is not a stream operation).  The
+        library records no memset nodes and allocates nothing, so every launch is capturable."""
+        if not self.training:
+            raise RuntimeError("constructed with training=False")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(steps):
+                B.vgg19_train_step(self.cfg, x, labels, self.packed, None, self.loss, self.logits, self.ws)
+        return g
+

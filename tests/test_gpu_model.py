@@ -218,3 +218,33 @@ def test_full_vgg19_train_step_batch100_is_mean_of_chunks():
         for l in range(len(src)):
             upd = new_big[k][l].astype(np.float64) - src[l].astype(np.float64)
             assert max_rel_err(upd, -0.01 * gb[k][l].numpy()) <= 1e-3, (k, l)
+
+
+def test_training_loop_as_one_graph_matches_eager_steps():
+    # K steps recorded once and replayed as a single launch must leave exactly the parameters that K eager
+    # steps leave (every kernel is deterministic); replayed several times, with eager work and
+    # synchronisations in between, and checked after every replay.
+    cfg = synth.tiny_config(seed=5)
+    K = 3
+    eager = Vgg19(B.F32, 2, 32, 32, 512, 10, lr=0.01, training=True)
+    graph = Vgg19(B.F32, 2, 32, 32, 512, 10, lr=0.01, training=True)
+    for m in (eager, graph):
+        m.pack(cfg.conv_w, cfg.conv_b, cfg.fc_w, cfg.fc_b)
+    x, lab = dev(cfg.x), dev(cfg.labels)
+    eager.train_step(x, lab)
+    graph.train_step(x, lab)      # warm-up before capture (and both models stay in step)
+    torch.cuda.synchronize()
+    g = graph.capture_train_steps(x, lab, K)
+    # capture only records: the parameters have not moved
+    assert torch.equal(eager.packed, graph.packed)
+    for replay in range(3):
+        g.replay()
+        for _ in range(K):
+            eager.train_step(x, lab)
+        torch.cuda.synchronize()
+        assert torch.equal(eager.packed, graph.packed), replay
+        assert torch.equal(eager.loss, graph.loss), replay
+        assert torch.equal(eager.logits, graph.logits), replay
+        # unrelated eager work between the replays
+        scratch = torch.rand((1 << 16,), device="cuda").sum().item()
+        assert scratch > 0
