@@ -26,6 +26,26 @@ CONV_SHAPES = [
 ]
 
 
+def _random_conv_shapes(count, seed=11):
+    """Seeded shapes that mix the kernels' variants: patch and linear tiles, 64- and 128-wide column tiles,
+    odd and even numbers of channel chunks, channel counts off the tile sizes, tiles that cross images."""
+    import random
+    rnd = random.Random(seed)
+    hw = [(5, 7), (16, 16), (17, 16), (28, 28), (30, 33), (56, 56), (14, 14), (32, 48), (9, 100), (64, 64), (2, 2), (112, 16), (3, 130)]
+    out = []
+    while len(out) < count:
+        H, W = rnd.choice(hw)
+        N = rnd.choice([1, 2, 3, 5, 9])
+        ci = rnd.choice([3, 8, 16, 24, 32, 40, 64, 96, 128, 160])
+        co = rnd.choice([8, 20, 64, 72, 128, 136, 192, 256, 320])
+        if N * H * W * ci * co * 9 <= 3e9:
+            out.append((N, H, W, ci, co))
+    return out
+
+
+RANDOM_CONV_SHAPES = _random_conv_shapes(24)
+
+
 def _pack(dtype, w, flip=0):
     Cout, Cin = w.shape[:2]
     rows, cols = (Cin, Cout) if flip else (Cout, Cin)
@@ -135,6 +155,15 @@ def test_conv3x3_bwd_weight(shape):
     B.vgg_conv3x3_bwd_weight(B.F32, N, H, W, Cin, Cout, x, g, dwp2, db, ws)
     torch.cuda.synchronize()
     assert torch.equal(dwp, dwp2)
+
+
+@pytest.mark.parametrize("shape", RANDOM_CONV_SHAPES)
+def test_conv3x3_random_shapes(shape):
+    for dtype in (B.F32, B.BF16):
+        test_conv3x3_fwd(dtype, shape)
+        test_conv3x3_bwd_data(dtype, shape)
+    if shape[4] % 4 == 0:
+        test_conv3x3_bwd_weight(shape)
 
 
 def test_pack_unpack_roundtrip_and_flip_layout():
