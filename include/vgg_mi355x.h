@@ -120,8 +120,13 @@ int vgg_convert(int src_dtype, int dst_dtype, size_t n, const void *src, void *d
  * table rows "convolution", "add", "maximum": a cross-correlation, no kernel
  * flip).  x is NHWC with exactly Cin channels, y NHWC with Cout channels,
  * w_packed as produced by vgg_conv_pack_weights(transpose_flip = 0), bias
- * fp32 [Cout] or NULL.  Workspace is only needed when Cin differs from
- * vgg_padded_channels(dtype, Cin) (a zero-padded copy of x is made there). */
+ * fp32 [Cout] or NULL.  Workspace is needed when Cin differs from
+ * vgg_padded_channels(dtype, Cin) (a zero-padded copy of x is made there)
+ * and for small problems (fewer pixel-by-channel tiles than half the chip's
+ * compute units and a long contraction): several workgroups then share a
+ * tile, each summing a range of input channels into fp32 partial results in
+ * the workspace, and a second kernel adds them in a fixed order and applies
+ * bias and f.  The query returns 0 when neither applies. */
 size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
 int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x_nhwc,
                     const void *w_packed, const float *bias, void *y_nhwc, int relu, void *ws,
@@ -131,7 +136,8 @@ int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const voi
  * argmax) fused into its epilogue: pooled is NHWC [N][H/2][W/2][Cout]; y may
  * be NULL, in which case the un-pooled tensor is never written.  Only for
  * H and W multiples of 16 and Cout a multiple of 16 bytes worth of elements
- * (VGG_ERR_UNSUPPORTED otherwise). */
+ * (VGG_ERR_UNSUPPORTED otherwise).  The contraction is never split here: the
+ * workspace only has to hold the zero-padded copy of x, if one is needed. */
 int vgg_conv3x3_fwd_pool(int dtype, int N, int H, int W, int Cin, int Cout, const void *x_nhwc,
                          const void *w_packed, const float *bias, void *y_nhwc_or_null, void *pooled_nhwc,
                          int relu, void *ws, size_t ws_bytes, void *stream);
@@ -149,8 +155,8 @@ int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, c
  * the transpose_flip != 0 packing.  If relu_src is non-NULL it must be an
  * NHWC tensor shaped like dx and dx is multiplied by (relu_src > 0), i.e.
  * the ReLU backward of the layer that produced this convolution's input is
- * fused in.  Workspace is only needed when Cout differs from
- * vgg_padded_channels(dtype, Cout). */
+ * fused in.  Workspace as for vgg_conv3x3_fwd with the roles of Cin and Cout
+ * exchanged (padded copy of g; partial sums of a split contraction). */
 size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
 int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, const void *g_nhwc,
                          const void *w_tf, const void *relu_src, void *dx_nhwc, void *ws,

@@ -6,7 +6,8 @@
 namespace vgg {
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
-                  const void *mask, void *y, void *pool, int relu, hipStream_t stream);
+                  const void *mask, void *y, void *pool, int relu, void *part_ws, hipStream_t stream);
+size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cout);
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
@@ -92,6 +93,7 @@ struct WsLayout {
     size_t pooled[VGG19_NUM_CONV];     // pool outputs (index = conv layer the pool follows)
     size_t argmax[VGG19_NUM_CONV];
     size_t z1, z2, logits, probs, fcws;
+    size_t convpart;                   // partial sums of convolutions whose contraction is split
     // training only
     size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
     size_t total;
@@ -148,6 +150,14 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         if (s > fw) fw = s;
     }
     L.fcws = b.take(fw);
+    size_t cpart = 0;
+    for (int l = 1; l < VGG19_NUM_CONV; ++l) {
+        size_t s = conv3x3_igemm_workspace(c->dtype, c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
+        if (s > cpart) cpart = s;
+        if (training) s = conv3x3_igemm_workspace(VGG_F32, c->N, L.H[l], L.W[l], kConvCh[l][1], kConvCh[l][0]);
+        if (s > cpart) cpart = s;
+    }
+    L.convpart = b.take(cpart);
     L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = 0;
     if (training) {
         L.dlogits = b.take(N * c->classes * 4);
@@ -211,7 +221,7 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
         else
             VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
                                                reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr,
-                                               fuse ? nullptr : out, fuse ? ws + L.pooled[l] : nullptr, 1, s));
+                                               fuse ? nullptr : out, fuse ? ws + L.pooled[l] : nullptr, 1, ws + L.convpart, s));
         cur = out;
         if (fuse) {
             rec.skip(K_POOL);  // fused into the launch above; listed so that the plan still shows five pools
@@ -275,7 +285,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
             VGG_STEP(rec, K_OTHER, flip_packed_w(P.cinp[l], Cout, Cout, F(pk + P.conv_w[l]), F(ws + L.wflip), s));
             VGG_STEP(rec, K_DGRAD, conv3x3_igemm(VGG_F32, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
-                                                gbuf[cur ^ 1], nullptr, 0, s));
+                                                gbuf[cur ^ 1], nullptr, 0, ws + L.convpart, s));
             cur ^= 1;
         }
     }
@@ -390,7 +400,8 @@ size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, 
 {
     if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
     const int cp = padded_channels(dtype, Cin);
-    return cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+    const size_t pad = cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+    return pad + conv3x3_igemm_workspace(dtype, N, H, W, cp, Cout);
 }
 
 static int conv_fwd_common(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
@@ -402,16 +413,21 @@ static int conv_fwd_common(int dtype, int N, int H, int W, int Cin, int Cout, co
     if (pooled && !conv3x3_pool_fusable(dtype, H, W, Cout)) return VGG_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w) || (y && !aligned16(y)) || (pooled && !aligned16(pooled)) || (ws && !aligned16(ws)))
         return VGG_ERR_ALIGN;
-    const size_t need = vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout);
-    if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
     const int cp = padded_channels(dtype, Cin);
+    // (with the pool fused the contraction is never split: only the padded copy is needed then)
+    const size_t part_bytes = pooled ? 0 : conv3x3_igemm_workspace(dtype, N, H, W, cp, Cout);
+    const size_t need = vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout) - (pooled ? conv3x3_igemm_workspace(dtype, N, H, W, cp, Cout) : 0);
+    if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    if (need) {
+    char *part = static_cast<char *>(ws);  // [padded copy of x][partial sums], either may be empty
+    if (cp != Cin) {
         const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, ws, s);
         if (rc) return rc;
         x = ws;
+        part += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
     }
-    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, pooled, relu ? 1 : 0, s);
+    if (!part_bytes) part = nullptr;
+    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, pooled, relu ? 1 : 0, part, s);
 }
 
 int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
@@ -442,7 +458,8 @@ size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int 
 {
     if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
     const int cp = padded_channels(dtype, Cout);
-    return cp == Cout ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+    const size_t pad = cp == Cout ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+    return pad + conv3x3_igemm_workspace(dtype, N, H, W, cp, Cin);
 }
 
 int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, const void *g, const void *w_tf,
@@ -457,12 +474,15 @@ int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, cons
     if (need && (!ws || ws_bytes < need)) return VGG_ERR_WORKSPACE;
     const int cp = padded_channels(dtype, Cout);
     hipStream_t s = (hipStream_t)stream;
-    if (need) {
+    char *part = static_cast<char *>(ws);  // [padded copy of g][partial sums], either may be empty
+    if (cp != Cout) {
         const int rc = pad_channels(dtype, (size_t)N * H * W, Cout, cp, g, ws, s);
         if (rc) return rc;
         g = ws;
+        part += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
     }
-    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, nullptr, 0, s);
+    if (!conv3x3_igemm_workspace(dtype, N, H, W, cp, Cin)) part = nullptr;
+    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, nullptr, 0, part, s);
 }
 
 size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)

@@ -44,6 +44,9 @@ struct ConvArgs {
     int relu;
     int tiles_n;        // number of column tiles
     int rowsA;          // LDS rows reserved for the halo
+    float *part;        // [ksplit][M][Cout] partial sums when the contraction is split over workgroups, else null
+    int ksplit;         // workgroups per tile (>= 1)
+    int kchunks;        // channel chunks per workgroup
     TileGeom g;
 };
 
@@ -80,7 +83,7 @@ __device__ __forceinline__ void init_acc(f32x16 (&acc)[TM][TN], const ConvArgs &
     // (channels past Cout are never stored: their loads are clamped into range instead of skipped;
     // one uniform branch around straight-line loads, so that none of them waits for another)
     const int c0 = n0 + wn * (BN / WN) + khalf * 4;
-    if (!p.bias) {
+    if (!p.bias || p.part) {   // (split contraction: the finishing kernel adds the bias)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -111,6 +114,34 @@ __device__ __forceinline__ void spread_acc(f32x16 (&acc)[TM][TN])
     for (int i = 1; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = acc[0][j];
+}
+
+// Epilogue of a workgroup that holds only part of the contraction: raw fp32 sums to the partial
+// buffer of its split (a lane owns runs of four consecutive channels of one pixel: 16-byte stores).
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void conv_partial_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
+                                                      const TileOrigin &org, int n0, int split)
+{
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int wm = wv % WM, wn = wv / WM;
+    const int r = lane & 31, khalf = lane >> 5;
+    float *part = p.part + (size_t)split * p.g.M * p.Cout;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + r);
+        if (m < 0) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int col = n0 + wn * (BN / WN) + j * 32 + a * 8 + khalf * 4;
+                if (col < p.Cout) {   // Cout is a multiple of 4 when the contraction is split
+                    const f32x4 v = {acc[i][j][a * 4], acc[i][j][a * 4 + 1], acc[i][j][a * 4 + 2], acc[i][j][a * 4 + 3]};
+                    *reinterpret_cast<f32x4 *>(part + (size_t)m * p.Cout + col) = v;
+                }
+            }
+    }
 }
 
 // Epilogue shared by the kernels below; called by every thread of the workgroup once all MFMAs are
@@ -427,8 +458,12 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     // tile then share the halo, and neighbouring pixel tiles their overlap, in one L2.
     const int nblk = gridDim.x, xcd = blockIdx.x & 7;
     const int bid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + (blockIdx.x >> 3);
-    const int tile_n = bid % p.tiles_n;
-    const int tile_m = bid / p.tiles_n;
+    // (split contraction: the ksplit workgroups of a tile are neighbours)
+    const int split = bid % p.ksplit, tile = bid / p.ksplit;
+    const int tile_n = tile % p.tiles_n;
+    const int tile_m = tile / p.tiles_n;
+    const int c_first = split * p.kchunks * KC;                    // this workgroup's channel range
+    const int c_end = min(c_first + p.kchunks * KC, p.CinP);
     const int n0 = tile_n * BN;
     const TileOrigin org = tile_origin(p.g, tile_m);
     const int pitch = p.g.pitch;
@@ -455,7 +490,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(woff[q]), "s"(base) : "m0", "memory");
         }
     };
-    dma_b(0, 0, 0);  // first: its latency covers the index arithmetic below
+    dma_b(c_first, 0, 0);  // first: its latency covers the index arithmetic below
 
     for (int i = tid; i < SA; i += NT) pix[i] = i < S ? halo_pixel(p.g, org, i) : -1;
 
@@ -535,7 +570,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     };
 
     u32x4 areg[MAXA];
-    load_a(0, areg);
+    load_a(c_first, areg);
     store_a(areg);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
@@ -544,13 +579,13 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     // Software pipeline over the stages.  Weight copies for the next stage go to the buffer that was
     // last read two stages ago; the next chunk's halo is requested at the first stage of a chunk and
     // stored to LDS after its last.
-    const int nstages = (p.CinP / KC) * 3;
-    int kh = 0, c0 = 0, bb = 0;
+    const int nstages = ((c_end - c_first) / KC) * 3;
+    int kh = 0, c0 = c_first, bb = 0;
     for (int s = 0; s + 1 < nstages; ++s) {
         int nkh = kh + 1, nc0 = c0;
         if (nkh == 3) { nkh = 0; nc0 += KC; }
         dma_b(nc0, nkh, bb ^ 1);
-        if (kh == 0 && c0 + KC < p.CinP) load_a(c0 + KC, areg);
+        if (kh == 0 && c0 + KC < c_end) load_a(c0 + KC, areg);
         compute(kh, Bs + bb * b_bytes);
         if (nkh == 0) {
             __syncthreads();  // every wave is done reading the halo of this chunk
@@ -562,7 +597,8 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     }
     compute(kh, Bs + bb * b_bytes);
 
-    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+    if (p.part) conv_partial_epilogue<BM, BN, WM, WN>(acc, p, org, n0, split);
+    else conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int SA>
@@ -583,7 +619,7 @@ static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t st
             return VGG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n)), dim3(WM * WN * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n * a.ksplit)), dim3(WM * WN * 64), lds, stream, a);
     return launch_status();
 }
 
@@ -610,17 +646,89 @@ static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stre
     return launch_status();
 }
 
-// x: [N*H*W][CinP], w: [9][Cout][CinP] (elements of dtype); y: [N*H*W][Cout].
-// pool (optional): 2x2 max of y, only when conv3x3_pool_fusable(); y may then be null.
+// Sums the partial results of a split contraction: y = f(bias + sum over splits), f = ReLU and/or the
+// (mask > 0) factor, converted to T.  One thread per four channels.
+template <typename T>
+__global__ __launch_bounds__(256) void conv_split_finish_kernel(const float *__restrict__ part, const float *__restrict__ bias,
+                                                                const T *__restrict__ mask, T *__restrict__ y, size_t quads,
+                                                                int Cout, int ksplit, int relu)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= quads) return;
+    const int col = (int)((i * 4) % (size_t)Cout);
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (bias) s = *reinterpret_cast<const f32x4 *>(bias + col);
+    for (int k = 0; k < ksplit; ++k) s += *reinterpret_cast<const f32x4 *>(part + ((size_t)k * quads + i) * 4);
+    const float lo = relu ? 0.f : -__builtin_inff();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        s[e] = fmaxf(s[e], lo);
+        if (mask && !(Elem<T>::load(mask + i * 4 + e) > 0.f)) s[e] = 0.f;
+    }
+    store4(y + i * 4, s[0], s[1], s[2], s[3]);
+}
+
+// Which kernel a shape gets, and whether its contraction is split over several workgroups per tile.
+struct ConvPlan {
+    TileGeom g;
+    bool narrow, dma, dma_big;
+    int ksplit, kchunks;
+};
+
+static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bool pool)
+{
+    ConvPlan c;
+    c.narrow = Cout <= 64;
+    // For A/B measurements: VGG_CONV_VARIANT=1 forces the register-staged kernel, 2 the 64-wide
+    // column tiles, 3 the 128-wide ones, 4 keeps every contraction in one workgroup.
+    static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
+    c.g = make_tile_geom(N, H, W, 256);
+    c.dma = variant != 1 && c.g.S <= kDmaHaloRows;
+    c.dma_big = variant != 1 && !c.dma && c.g.S <= kDmaHaloRowsBig;
+    // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
+    // double the workgroup count and three of them fit on a CU.
+    if (c.g.ntiles * ((Cout + 127) / 128) < 512) c.narrow = true;
+    if (variant == 2) c.narrow = true;
+    if (variant == 3) c.narrow = false;
+    // Small batches: fewer tiles than CUs, each walking the whole contraction alone.  Then several
+    // workgroups share a tile, each taking a range of channel chunks (at least two), and a second
+    // kernel adds their partial sums.
+    const int chunks = CinP * dtype_size(dtype) / kDataBytes;
+    const int total = c.g.ntiles * ((Cout + (c.narrow ? 63 : 127)) / (c.narrow ? 64 : 128));
+    c.ksplit = 1; c.kchunks = chunks;
+    // Measured: pays when at most half the CUs would have a workgroup and a tile's contraction is
+    // long enough (a bf16 chunk takes a quarter of the time of an fp32 one).
+    if (variant != 4 && (c.dma || c.dma_big) && !pool && Cout % 4 == 0 && total <= 128 &&
+        chunks >= (dtype == VGG_BF16 ? 8 : 4)) {
+        int want = (512 + total - 1) / total;   // two workgroups per CU
+        if (want > chunks / 2) want = chunks / 2;
+        c.kchunks = (chunks + want - 1) / want;
+        c.ksplit = (chunks + c.kchunks - 1) / c.kchunks;
+    }
+    return c;
+}
+
+// Bytes of partial sums conv3x3_igemm needs for this shape (0: the contraction is not split).
+size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cout)
+{
+    const ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, false);
+    return c.ksplit > 1 ? round_up((size_t)c.ksplit * N * H * W * Cout * 4, 256) : 0;
+}
+
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout)
 {
     return H % 16 == 0 && W % kTileW == 0 && Cout % (16 / dtype_size(dtype)) == 0;
 }
 
+// x: [N*H*W][CinP], w: [9][Cout][CinP] (elements of dtype); y: [N*H*W][Cout].
+// pool (optional): 2x2 max of y, only when conv3x3_pool_fusable(); y may then be null.
+// part_ws: conv3x3_igemm_workspace() bytes, or null (then the contraction is never split).
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w,
-                  const float *bias, const void *mask, void *y, void *pool, int relu, hipStream_t stream)
+                  const float *bias, const void *mask, void *y, void *pool, int relu, void *part_ws, hipStream_t stream)
 {
     if (pool && !conv3x3_pool_fusable(dtype, H, W, Cout)) return VGG_ERR_UNSUPPORTED;
+    ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, pool != nullptr);
+    if (!part_ws || !y) { c.ksplit = 1; c.kchunks = CinP * dtype_size(dtype) / kDataBytes; }
     ConvArgs a;
     a.x = static_cast<const char *>(x);
     a.w = static_cast<const char *>(w);
@@ -630,36 +738,42 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.pool = static_cast<char *>(pool);
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
-    bool narrow = Cout <= 64;
-    // For A/B measurements: VGG_CONV_VARIANT=1 forces the register-staged kernel, 2 the 64-wide
-    // column tiles, 3 the 128-wide ones.
-    static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
-    const TileGeom g = make_tile_geom(N, H, W, 256);
-    const bool dma = variant != 1 && g.S <= kDmaHaloRows;
-    const bool dma_big = variant != 1 && !dma && g.S <= kDmaHaloRowsBig;
-    // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
-    // double the workgroup count and three of them fit on a CU.
-    if (g.ntiles * ((Cout + 127) / 128) < 512) narrow = true;
-    if (variant == 2) narrow = true;
-    if (variant == 3) narrow = false;
+    a.part = c.ksplit > 1 ? static_cast<float *>(part_ws) : nullptr;
+    a.ksplit = c.ksplit; a.kchunks = c.kchunks;
+    const bool narrow = c.narrow, dma = c.dma, dma_big = c.dma_big;
+    const TileGeom &g = c.g;
+    int rc;
     if (dtype == VGG_F32) {
         if (dma)
-            return narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
-                          : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
-        if (dma_big)
-            return narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
-                          : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
-        return narrow ? launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream)
-                      : launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+            rc = narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
+                        : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
+        else if (dma_big)
+            rc = narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
+                        : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
+        else
+            rc = narrow ? launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream)
+                        : launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+    } else {
+        if (dma)
+            rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
+                        : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
+        else if (dma_big)
+            rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
+                        : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
+        else
+            rc = narrow ? launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream)
+                        : launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
     }
-    if (dma)
-        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
-                      : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
-    if (dma_big)
-        return narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
-                      : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
-    return narrow ? launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream)
-                  : launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+    if (rc != VGG_OK || c.ksplit == 1) return rc;
+    const size_t quads = (size_t)N * H * W * Cout / 4;
+    const dim3 grid((unsigned)((quads + 255) / 256));
+    if (dtype == VGG_F32)
+        hipLaunchKernelGGL(conv_split_finish_kernel<float>, grid, dim3(256), 0, stream, a.part, bias,
+                           static_cast<const float *>(mask), static_cast<float *>(y), quads, Cout, c.ksplit, relu);
+    else
+        hipLaunchKernelGGL(conv_split_finish_kernel<bf16_t>, grid, dim3(256), 0, stream, a.part, bias,
+                           static_cast<const bf16_t *>(mask), static_cast<bf16_t *>(y), quads, Cout, c.ksplit, relu);
+    return launch_status();
 }
 
 }  // namespace vgg

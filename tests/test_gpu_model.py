@@ -184,8 +184,11 @@ def test_full_vgg19_train_step_224_vs_oracle_batch2():
 def test_full_vgg19_train_step_batch100_is_mean_of_chunks():
     # The loss is a mean over images, so the batch-100 gradient equals the mean of the gradients of
     # five batch-20 steps from the same parameters (a property that holds at any size); the batch-2
-    # test above ties the same kernels at the same spatial sizes to the oracle.
-    N, chunk = 100, 20
+    # test above ties the same kernels at the same spatial sizes to the oracle.  The chunks must run
+    # the same arithmetic per image as the full batch: a ReLU or pooling decision that rounding
+    # flips moves a gradient by far more than the tolerance.  Halves do (below roughly 40 images
+    # the 14x14 layers split their contraction over several workgroups, another summation order).
+    N, chunk = 100, 50
     inp = synth.full_config(N, seed=2)
     big = Vgg19(B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
     big.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)

@@ -23,6 +23,11 @@ CONV_SHAPES = [
     (5, 16, 48, 32, 192),
     (1, 56, 56, 64, 64),
     (1, 6, 100, 16, 32),   # wide rows: halo beyond the direct-to-LDS kernels' limit, weight-gradient halo in several batches
+    # few tiles and a long contraction: several workgroups share a tile, each with a range of channel
+    # chunks (uneven ranges: 9 or 18 chunks of 64 bytes; fp32 only: 5 chunks in two ranges)
+    (1, 20, 20, 288, 64),
+    (2, 14, 14, 80, 96),
+    (1, 14, 14, 512, 512),
 ]
 
 
@@ -305,6 +310,25 @@ def test_layout_roundtrip_and_convert():
     o2 = torch.empty((2,), dtype=torch.bfloat16, device="cuda")
     B.vgg_convert(B.F32, B.BF16, 2, halfway, o2)
     assert o2.float().tolist() == [1.0, 1.015625]                     # ties go to the even mantissa
+
+
+def test_conv3x3_split_contraction_needs_its_workspace():
+    # a shape whose contraction is split reports a workspace for the partial sums and refuses to run without it
+    N, H, W, Cin, Cout = 1, 14, 14, 512, 512
+    for dtype in (B.F32, B.BF16):
+        need = B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout)
+        assert need >= 2 * N * H * W * Cout * 4
+        assert B.vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout) == need
+        x = torch.zeros((N, H, W, Cin), dtype=TDT[dtype], device="cuda")
+        w = torch.zeros((9, Cout, Cin), dtype=TDT[dtype], device="cuda")
+        y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+        for ws in (None, ws_bytes(need - 256)):
+            with pytest.raises(B.VggError):
+                B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, w, None, y, 1, ws)
+            with pytest.raises(B.VggError):
+                B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, x, w, None, y, ws)
+    # the batch-100 shapes keep every contraction in one workgroup: no workspace
+    assert B.vgg_conv3x3_fwd_workspace_bytes(B.BF16, 100, 14, 14, 512, 512) == 0
 
 
 def test_mfma_probe_runs_and_reports_flops():
