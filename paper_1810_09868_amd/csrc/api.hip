@@ -12,6 +12,9 @@ bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
+size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout);
+int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
+                       void *ws, hipStream_t stream);
 int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
                   hipStream_t stream);
 size_t mfma_probe_sink_bytes();
@@ -487,10 +490,10 @@ int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, cons
 
 size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)
 {
-    if (dtype != VGG_F32 || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
+    if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
     const int cp = padded_channels(dtype, Cin);
-    size_t pad = cp == Cin ? 0 : round_up((size_t)N * H * W * cp * 4, 256);
-    return pad + conv3x3_wgrad_workspace(N, H, W, cp, Cout);
+    size_t pad = cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+    return pad + (dtype == VGG_F32 ? conv3x3_wgrad_workspace(N, H, W, cp, Cout) : conv3x3_wgrad_bf16_workspace(N, H, W, cp, Cout));
 }
 
 int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *g, float *dw,
@@ -498,9 +501,8 @@ int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, co
 {
     if (!x || !g || !dw) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
-    if (dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
     if (!conv_shape_ok(N, H, W, Cin, Cout)) return VGG_ERR_SHAPE;
-    if (Cout % 4) return VGG_ERR_UNSUPPORTED;
+    if (Cout % (dtype == VGG_F32 ? 4 : 8)) return VGG_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(g) || !aligned16(dw) || (db && !aligned16(db)) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
     const size_t need = vgg_conv3x3_bwd_weight_workspace_bytes(dtype, N, H, W, Cin, Cout);
     if (!ws || ws_bytes < need) return VGG_ERR_WORKSPACE;
@@ -511,8 +513,10 @@ int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, co
         const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, wsp, s);
         if (rc) return rc;
         x = wsp;
-        wsp += round_up((size_t)N * H * W * cp * 4, 256);
+        wsp += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
     }
+    if (dtype == VGG_BF16)
+        return conv3x3_wgrad_bf16(N, H, W, cp, Cout, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), dw, db, wsp, s);
     return conv3x3_wgrad(N, H, W, Cin, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp, s);
 }
 

@@ -422,6 +422,12 @@ static void launch_reduce(const float *part, float *out, size_t n, int splits, h
         hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, part, out, n, splits);
 }
 
+// (also used by the bf16 weight-gradient kernel)
+void wgrad_launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream)
+{
+    launch_reduce(part, out, n, splits, stream);
+}
+
 static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a, bool thin = false)
 {
     a.geo = make_tile_geom(N, H, W, kPK);

@@ -1,0 +1,263 @@
+// Weight gradient of the 3x3 convolution with bf16 operands and fp32 sums (the matrix unit's
+// bf16 x bf16 -> fp32 numerics of the paper's accelerator, applied to the backward pass), gfx950, NHWC.
+//
+//   dw[t][co][ci] = sum_m g[m][co] * x[m + tap t][ci],   db[co] = sum_m g[m][co]
+//
+// (backward column of the appendix table: one more "convolution" per layer, plus a "reduce" for
+// the bias).  GEMM view per tap: rows = co, columns = ci, contraction over the pixels m.
+//
+// v_mfma_f32_32x32x16_bf16 wants, per lane, eight consecutive contraction indices of one row: eight
+// pixels of one channel.  Memory and LDS hold the opposite (a pixel's channels are contiguous), so
+// the fragments are fetched with the LDS transpose read ds_read_b64_tr_b16: within 16 lanes, lane i
+// receives element i%4 of the four 8-byte chunks that lanes i/4, i/4+4, i/4+8, i/4+12 point at.
+// Lane s of a group points at pixel s/4, channels 4(s%4).. of a 16-channel run: lane i then holds four
+// consecutive pixels of channel i.  Two such reads make a fragment; a tap only shifts the pixel rows
+// that the lanes point at, so all nine taps are served from one staged halo.
+//
+// A tile is a 4 x 16 patch of one image (patches may stick out at the right and bottom edge; what
+// is outside reads as zero) and its 6 x 18 halo: MFMA step s of a tile contracts the 16 pixels of
+// patch row s.  LDS rows are 160 bytes (64 channels + 32 bytes of padding: four consecutive pixel
+// rows then start 32 bytes apart in the banks and the transpose reads are conflict-free); since the
+// patch geometry is fixed, every fragment address is one per-lane base plus an immediate.
+//
+// A workgroup (4 waves) owns a 64(co) x 64(ci) block of all nine taps and a range of tiles.  Wave
+// = (ci half) x (taps 0-4 | taps 5-8); it multiplies both 32-row co tiles with its five or four x
+// fragments per step.  Staging: global_load_lds_dwordx4 straight into one of two LDS buffers, one
+// barrier per tile.  The block writes partial sums; a second kernel adds the partials of all
+// splits in a fixed order, so the result does not depend on scheduling.  The bias gradient comes
+// from two extra MFMAs per step against a fragment of ones, in the blocks of the first ci tile.
+#include "common.h"
+
+namespace vgg {
+
+void wgrad_launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream);
+
+namespace {
+
+constexpr int kTH = 4, kTW = 16;                 // patch
+constexpr int kP = kTH * kTW;                    // pixels per tile
+constexpr int kHW = kTW + 2;                     // halo width
+constexpr int kHaloRows = (kTH + 2) * kHW;       // 108
+constexpr int kRow = 160;                        // LDS bytes per pixel row
+constexpr int kGBytes = kP * kRow;               // 10240
+constexpr int kXBytes = kHaloRows * kRow;        // 17280
+constexpr int kNW = 4;                           // waves
+constexpr int kOps = (kGBytes + kXBytes + kNW * 1024 - 1) / (kNW * 1024);  // copies per lane and tile: 7
+constexpr int kBuf = kOps * kNW * 1024;          // 28672 bytes per buffer (tail never read)
+constexpr int kCO = 64, kCI = 64;
+
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+__device__ const u32x4_t kZero16[1] = {};        // what a segment outside the tensors reads
+
+struct WgradBf16Args {
+    const bf16_t *x;  // [M][CinP]
+    const bf16_t *g;  // [M][Cout]
+    float *part;      // [splits][9][Cout][CinP]
+    float *dbpart;    // [splits][Cout] or null
+    int N, H, W, CinP, Cout;
+    int tiles_co, tiles_ci, splits, tiles_per_split, ntiles;
+    int tiles_w, tiles_hw;
+    FastDiv dTilesW, dTilesHW;
+};
+
+__device__ __forceinline__ bf16x8 tr_fragment(const char *lds_lo, const char *lds_hi)
+{
+    typedef __attribute__((address_space(3))) s16x4 *lp;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)lds_lo);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)lds_hi);
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Taps [T0, T0 + NT) of one wave.  DB: this wave also sums g over the pixels.
+template <int T0, int NT, bool DB>
+__device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *smem, int tco, int tci, int split)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wi = wv & 1;                                   // ci half of this wave
+    const int co0 = tco * kCO, ci0 = tci * kCI;
+
+    f32x16 acc[2][NT];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[c][t][e] = 0.f;
+    f32x16 accb[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) accb[c][e] = 0.f;
+
+    // Copies: lane covers bytes [16 L, 16 L + 16) of a buffer, L = 256 k + tid, k < kOps.  Which
+    // tensor, pixel (relative to the patch origin) and channel segment that is never changes.
+    int cp_dy[kOps], cp_dx[kOps], cp_col[kOps];  // col < 0: zeros
+    bool cp_g[kOps];
+#pragma unroll
+    for (int k = 0; k < kOps; ++k) {
+        const int off = (k * kNW * 64 + tid) * 16;
+        const bool isg = off < kGBytes;
+        const int o = isg ? off : off - kGBytes;
+        const int row = o / kRow, seg = (o - row * kRow) >> 4;
+        cp_g[k] = isg;
+        if (isg) { cp_dy[k] = row / kTW; cp_dx[k] = row % kTW; }
+        else { cp_dy[k] = row / kHW - 1; cp_dx[k] = row % kHW - 1; }
+        const int col = (isg ? co0 : ci0) + seg * 8;
+        const bool ok = seg < 8 && (isg || row < kHaloRows) && col < (isg ? p.Cout : p.CinP);
+        cp_col[k] = ok ? col : -1;
+    }
+    auto issue = [&](int tile, char *base) __attribute__((always_inline)) {
+        const int n = fast_div(tile, p.dTilesHW);
+        const int rem = tile - n * p.tiles_hw;
+        const int ty = fast_div(rem, p.dTilesW);
+        const int h0 = ty * kTH, w0 = (rem - ty * p.tiles_w) * kTW;
+#pragma unroll
+        for (int k = 0; k < kOps; ++k) {
+            const int h = h0 + cp_dy[k], w = w0 + cp_dx[k];
+            const bool ok = cp_col[k] >= 0 && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
+            const size_t pix = (size_t)((n * p.H + h) * p.W + w);
+            const bf16_t *src = cp_g[k] ? p.g + pix * p.Cout + cp_col[k] : p.x + pix * p.CinP + cp_col[k];
+            if (!ok) src = reinterpret_cast<const bf16_t *>(kZero16);
+            const unsigned d = __builtin_amdgcn_readfirstlane(
+                (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(base + (k * kNW + wv) * 1024));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(d), "v"(src) : "m0", "memory");
+        }
+    };
+
+    // Fragment addresses.  Lane 16 G + i points at pixel dx = 8 (G >> 1) + (i >> 2) (+4 for the second
+    // read) of a patch row and at the 8-byte chunk i & 3 of the 32-byte run G & 1 of a 32-channel tile.
+    const int G = lane >> 4, i = lane & 15;
+    const int lane_off = (8 * (G >> 1) + (i >> 2)) * kRow + (G & 1) * 32 + (i & 3) * 8;
+    const int g_off = lane_off;                              // + co tile * 64 + (16 s + 4 h) * kRow
+    const int x_off = kGBytes + lane_off + wi * 64;          // + ((s + kh) * 18 + kw + 4 h) * kRow
+
+    const int t_begin = split * p.tiles_per_split;
+    const int t_end = min(t_begin + p.tiles_per_split, p.ntiles);
+    if (t_begin < t_end) issue(t_begin, smem);
+
+    const s16x8 ones_v = {0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_v);
+
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const int buf = (tile - t_begin) & 1;
+        // This tile's copies have landed (each wave waits for its own, the barrier publishes all),
+        // and every wave is done with the other buffer, which the next copies overwrite.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
+        if (tile + 1 < t_end) issue(tile + 1, smem + (buf ^ 1) * kBuf);
+        const char *B = smem + buf * kBuf;
+#pragma unroll
+        for (int s = 0; s < kTH; ++s) {
+            bf16x8 gf[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                gf[c] = tr_fragment(B + g_off + c * 64 + (16 * s) * kRow, B + g_off + c * 64 + (16 * s + 4) * kRow);
+            if (DB) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) accb[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], ones, accb[c], 0, 0, 0);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int kh = (T0 + t) / 3, kw = (T0 + t) % 3;
+                const int ro = ((s + kh) * kHW + kw) * kRow;
+                const bf16x8 xf = tr_fragment(B + x_off + ro, B + x_off + ro + 4 * kRow);
+#pragma unroll
+                for (int c = 0; c < 2; ++c) acc[c][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], xf, acc[c][t], 0, 0, 0);
+            }
+        }
+    }
+
+    // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (co), column l%32 (ci)
+    const int r = lane & 31, kp = lane >> 5;
+    const int ci = ci0 + wi * 32 + r;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int co = co0 + c * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+                if (co < p.Cout && ci < p.CinP)
+                    p.part[(((size_t)split * 9 + T0 + t) * p.Cout + co) * p.CinP + ci] = acc[c][t][e];
+            }
+    if (DB && r == 0) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int co = co0 + c * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+                if (co < p.Cout) p.dbpart[(size_t)split * p.Cout + co] = accb[c][e];
+            }
+    }
+}
+
+__global__ __launch_bounds__(kNW * 64, 2) void conv3x3_wgrad_bf16_kernel(WgradBf16Args p)
+{
+    extern __shared__ __align__(16) char smem[];
+    // Workgroup b runs on XCD b % 8 and every XCD has its own L2: renumber so that an XCD works
+    // through whole splits, whose blocks all read the same tiles.
+    const int nblk = gridDim.x, xcd = blockIdx.x & 7;
+    int b = xcd * (nblk >> 3) + min(xcd, nblk & 7) + (blockIdx.x >> 3);
+    const int tco = b % p.tiles_co; b /= p.tiles_co;
+    const int tci = b % p.tiles_ci; b /= p.tiles_ci;
+    const int split = b;
+    // (wave-uniform branches: all bodies execute the same sequence of barriers)
+    const int group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (group == 0) wgrad_bf16_body<0, 5, false>(p, smem, tco, tci, split);
+    else if (p.dbpart && tci == 0 && wave == 2) wgrad_bf16_body<5, 4, true>(p, smem, tco, tci, split);
+    else wgrad_bf16_body<5, 4, false>(p, smem, tco, tci, split);
+}
+
+void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
+{
+    a.N = N; a.H = H; a.W = W; a.CinP = CinP; a.Cout = Cout;
+    a.tiles_w = (W + kTW - 1) / kTW;
+    a.tiles_hw = a.tiles_w * ((H + kTH - 1) / kTH);
+    a.ntiles = N * a.tiles_hw;
+    a.dTilesW = make_fast_div(a.tiles_w);
+    a.dTilesHW = make_fast_div(a.tiles_hw);
+    a.tiles_co = (Cout + kCO - 1) / kCO;
+    a.tiles_ci = (CinP + kCI - 1) / kCI;
+    const int groups = a.tiles_co * a.tiles_ci;
+    int splits = (1024 + groups - 1) / groups;   // two resident workgroups per CU, two rounds
+    if (splits > a.ntiles) splits = a.ntiles;
+    if (splits < 1) splits = 1;
+    a.tiles_per_split = (a.ntiles + splits - 1) / splits;
+    a.splits = (a.ntiles + a.tiles_per_split - 1) / a.tiles_per_split;
+}
+
+}  // namespace
+
+size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
+{
+    WgradBf16Args a;
+    wgrad_bf16_plan(N, H, W, CinP, Cout, a);
+    return round_up((size_t)a.splits * 9 * Cout * CinP * 4, 256) + round_up((size_t)a.splits * Cout * 4, 256);
+}
+
+// x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
+// Cout must be a multiple of 8 and CinP of 32 (16-byte channel segments).
+int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
+                       void *ws, hipStream_t stream)
+{
+    if (Cout % 8 || CinP % 8) return VGG_ERR_UNSUPPORTED;
+    if ((long long)N * H * W >= (1ll << 31) / 2) return VGG_ERR_UNSUPPORTED;
+    WgradBf16Args a;
+    wgrad_bf16_plan(N, H, W, CinP, Cout, a);
+    a.x = x; a.g = g;
+    const size_t nw = (size_t)9 * Cout * CinP;
+    a.part = static_cast<float *>(ws);
+    a.dbpart = db ? reinterpret_cast<float *>(static_cast<char *>(ws) + round_up((size_t)a.splits * nw * 4, 256)) : nullptr;
+    const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
+    hipLaunchKernelGGL(conv3x3_wgrad_bf16_kernel, grid, dim3(kNW * 64), 2 * kBuf, stream, a);
+    if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
+    wgrad_launch_reduce(a.part, dw, nw, a.splits, stream);
+    if (db) wgrad_launch_reduce(a.dbpart, db, (size_t)Cout, a.splits, stream);
+    return launch_status();
+}
+
+}  // namespace vgg

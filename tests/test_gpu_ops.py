@@ -137,27 +137,41 @@ def test_conv3x3_bwd_data(dtype, shape):
     assert max_rel_err(from_nhwc(dx), ref * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-def test_conv3x3_bwd_weight(shape):
+def test_conv3x3_bwd_weight(dtype, shape):
+    _check_bwd_weight(dtype, shape, seed=sum(shape) + 2)
+
+
+def _check_bwd_weight(dtype, shape, seed):
+    """fp32, or bf16 operands (x and g rounded to bf16, fp32 sums and fp32 result)."""
     N, H, W, Cin, Cout = shape
-    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape) + 2)
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=seed)
     dw_ref, db_ref = R.conv3x3_bwd_weight(d["x"], d["dy"])
-    x = to_nhwc(d["x"], B.F32)
-    g = to_nhwc(d["dy"], B.F32)
-    cp = B.vgg_padded_channels(B.F32, Cin)
+    x = to_nhwc(d["x"], dtype)
+    g = to_nhwc(d["dy"], dtype)
+    cp = B.vgg_padded_channels(dtype, Cin)
     dwp = torch.full((9, Cout, cp), float("nan"), device="cuda")
     db = torch.empty((Cout,), device="cuda")
-    ws = ws_bytes(B.vgg_conv3x3_bwd_weight_workspace_bytes(B.F32, N, H, W, Cin, Cout))
-    B.vgg_conv3x3_bwd_weight(B.F32, N, H, W, Cin, Cout, x, g, dwp, db, ws)
-    dw = torch.empty((Cout, Cin, 3, 3), device="cuda")
-    B.vgg_conv_unpack_weights(Cin, Cout, dwp, dw)
+    ws = ws_bytes(B.vgg_conv3x3_bwd_weight_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    if dtype == B.BF16 and Cout % 8:
+        with pytest.raises(B.VggError):      # 16-byte channel segments of g
+            B.vgg_conv3x3_bwd_weight(dtype, N, H, W, Cin, Cout, x, g, dwp, db, ws)
+        return
+    B.vgg_conv3x3_bwd_weight(dtype, N, H, W, Cin, Cout, x, g, dwp, db, ws)
     torch.cuda.synchronize()
-    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[B.F32]
-    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[B.F32]
+    dw = dwp[:, :, :Cin].reshape(3, 3, Cout, Cin).permute(2, 3, 0, 1)    # [t][co][ci] -> [co][ci][kh][kw]
+    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[dtype]
+    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[dtype]
     assert (dwp[:, :, Cin:] == 0).all()     # padding channels get exact zeros
+    if dtype == B.F32:
+        dw2 = torch.empty((Cout, Cin, 3, 3), device="cuda")
+        B.vgg_conv_unpack_weights(Cin, Cout, dwp, dw2)
+        torch.cuda.synchronize()
+        assert torch.equal(dw2, dw)
     # run-to-run reproducibility of the split reduction
     dwp2 = torch.empty_like(dwp)
-    B.vgg_conv3x3_bwd_weight(B.F32, N, H, W, Cin, Cout, x, g, dwp2, db, ws)
+    B.vgg_conv3x3_bwd_weight(dtype, N, H, W, Cin, Cout, x, g, dwp2, db, ws)
     torch.cuda.synchronize()
     assert torch.equal(dwp, dwp2)
 
@@ -168,7 +182,8 @@ def test_conv3x3_random_shapes(shape):
         test_conv3x3_fwd(dtype, shape)
         test_conv3x3_bwd_data(dtype, shape)
     if shape[4] % 4 == 0:
-        test_conv3x3_bwd_weight(shape)
+        _check_bwd_weight(B.F32, shape, seed=sum(shape) + 2)
+        _check_bwd_weight(B.BF16, shape, seed=sum(shape) + 2)
 
 
 def test_pack_unpack_roundtrip_and_flip_layout():
