@@ -52,7 +52,7 @@ typedef enum vgg_status {
     VGG_ERR_ALIGN = -4,       /* a tensor pointer is not 16-byte aligned */
     VGG_ERR_WORKSPACE = -5,   /* ws is NULL or ws_bytes too small */
     VGG_ERR_LAUNCH = -6,      /* HIP reported an error when a kernel was enqueued */
-    VGG_ERR_UNSUPPORTED = -7  /* valid request the library does not implement (e.g. bf16 training) */
+    VGG_ERR_UNSUPPORTED = -7  /* valid request the library does not implement (e.g. bf16 training without master copy) */
 } vgg_status;
 
 typedef enum vgg_dtype { VGG_F32 = 0, VGG_BF16 = 1 } vgg_dtype;
@@ -71,8 +71,15 @@ typedef struct vgg_config {
     int fc_hidden;  /* 4096 for the full model, 512 for the tiny one */
     int classes;    /* 1000 / 10 */
     float lr;       /* SGD step size used by vgg19_train_step */
-    int flags;      /* reserved, must be 0 */
+    int flags;      /* 0 or VGG_FLAG_FP32_MASTER */
 } vgg_config;
+
+/* dtype VGG_BF16 only: the packed parameter block carries, behind the bf16
+ * parameters that the kernels read, an fp32 master copy of every tensor.
+ * vgg19_train_step needs it for bf16 (the update is applied to the master and
+ * the bf16 copy refreshed from it); vgg19_unpack_params reads it back;
+ * vgg19_forward ignores it. */
+#define VGG_FLAG_FP32_MASTER 1
 
 /* Canonical fp32 parameter (or gradient) set: device pointers. */
 typedef struct vgg19_params {
@@ -163,9 +170,12 @@ int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, cons
                          size_t ws_bytes, void *stream);
 
 /* dw[t,co,ci] = sum_{n,h,w} g[n,h,w,co] * x[n,h+kh-1,w+kw-1,ci],
- * db[co] = sum_{n,h,w} g[n,h,w,co].  fp32 only.  dw is written in the packed
- * layout [9][Cout][CinP] (padding entries zero), db is [Cout] or NULL; Cout
- * must be a multiple of 4 (VGG_ERR_UNSUPPORTED otherwise).  The
+ * db[co] = sum_{n,h,w} g[n,h,w,co].  x and g are NHWC in `dtype`; dw and db
+ * are always fp32 (VGG_BF16: bf16 products, fp32 sums, as on the paper's
+ * accelerator).  dw is written in the packed layout [9][Cout][CinP] with
+ * CinP = vgg_padded_channels(dtype, Cin) (padding entries zero), db is
+ * [Cout] or NULL; Cout must be a multiple of 4 (VGG_F32) or 8 (VGG_BF16),
+ * VGG_ERR_UNSUPPORTED otherwise.  The
  * pixel sum is split over workgroups; partial sums go to ws and a second
  * kernel adds them in a fixed order, so results are reproducible run to run. */
 size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout);
@@ -229,7 +239,8 @@ size_t vgg19_train_workspace_bytes(const vgg_config *cfg);
 
 /* canonical fp32 -> packed block (convolution weights packed and converted,
  * the first dense layer's columns permuted from C,H,W to H,W,C order, biases
- * fp32), and back (fp32 configs only). */
+ * fp32; with VGG_FLAG_FP32_MASTER the fp32 master copy as well), and back
+ * (fp32 configs, or bf16 with VGG_FLAG_FP32_MASTER: the master copy). */
 int vgg19_pack_params(const vgg_config *cfg, const vgg19_params *canonical, void *packed,
                       size_t packed_bytes, void *stream);
 int vgg19_unpack_params(const vgg_config *cfg, const void *packed, size_t packed_bytes,
@@ -244,8 +255,12 @@ int vgg19_forward(const vgg_config *cfg, const float *x_nchw, const void *packed
 /* One training step (section "VGG19 backward pass", with mean softmax
  * cross-entropy in place of the paper's stand-in sum, whose gradient through
  * softmax is identically zero): forward, loss, full backward, then
- * theta <- theta - cfg->lr * grad on the packed block in place.  fp32
- * configs only.  labels int32 [N].  grads_or_null, when given, receives the
+ * theta <- theta - cfg->lr * grad on the packed block in place.  VGG_F32,
+ * or VGG_BF16 with VGG_FLAG_FP32_MASTER: activations, their gradients and
+ * the weights the convolutions read are bf16, all sums fp32 (the matrix
+ * unit's bf16 x bf16 -> fp32 of the paper's accelerator); the dense layers'
+ * backward runs in fp32 from the master weights; the update goes to the fp32
+ * master copy and the bf16 copy is refreshed from it.  labels int32 [N].  grads_or_null, when given, receives the
  * 38 gradient tensors in canonical layout.  loss (1 float) and logits
  * ([N][classes]) may be NULL. */
 int vgg19_train_step(const vgg_config *cfg, const float *x_nchw, const int32_t *labels,

@@ -178,47 +178,64 @@ def sgd(theta, grad, lr: float) -> np.ndarray:
     return theta
 
 
+def round_bf16(a) -> np.ndarray:
+    """Nearest bfloat16 value (8 significant bits, ties to even), returned as
+    float64: the operand precision of the accelerator's matrix unit, which
+    multiplies bfloat16 values and accumulates in float32 (section on the TPU
+    hardware).  Exponent range is float32's, so for the magnitudes that occur
+    here no overflow or underflow handling is needed."""
+    a = _f64(a)
+    m, e = np.frexp(a)                       # a = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0), e - 8)   # np.rint rounds halves to even
+
+
 # --------------------------------------------------------------------------
 # Whole model
 # --------------------------------------------------------------------------
 
 def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: Sequence,
-                  keep: bool = False) -> Dict[str, object]:
+                  keep: bool = False, operand_round=None) -> Dict[str, object]:
     """images [N,3,H,W] -> logits, probs (and every intermediate when keep).
 
     Order of operations: for each of the 16 convolutions, cross-correlate,
     add bias, clamp at zero; after convolutions 2, 4, 8, 12 and 16 take the
     2x2 maximum; flatten in C,H,W order; dense+ReLU, dense+ReLU, dense;
     softmax over the classes of each image.
+
+    ``operand_round`` (e.g. round_bf16) models reduced-precision matrix
+    operands: it is applied to everything that enters a product (the images,
+    every weight tensor, every layer's output after its ReLU); biases, sums,
+    the logits and the softmax stay in full precision.
     """
+    rd = operand_round if operand_round is not None else (lambda a: a)
     assert len(conv_w) == 16 and len(fc_w) == 3
     out: Dict[str, object] = {}
     acts: List[np.ndarray] = []      # input of every conv layer
     pres: List[np.ndarray] = []      # pre-activation (bias added, before ReLU) of every conv layer
     ys: List[np.ndarray] = []        # post-ReLU output of every conv layer
     args: Dict[int, np.ndarray] = {}
-    h = _f64(x)
+    h = rd(_f64(x))
     for l, (cin, cout) in enumerate(_CONV_CHANNELS):
         assert conv_w[l].shape == (cout, cin, 3, 3)
         if keep:
             acts.append(h)
-            pre = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=False)
+            pre = conv3x3_fwd(h, rd(conv_w[l]), conv_b[l], relu=False)
             pres.append(pre)
-            h = np.maximum(pre, 0.0)
+            h = rd(np.maximum(pre, 0.0))
             ys.append(h)
         else:
-            h = conv3x3_fwd(h, conv_w[l], conv_b[l], relu=True)
+            h = rd(conv3x3_fwd(h, rd(conv_w[l]), conv_b[l], relu=True))
         if l in _POOL_AFTER:
             h, a = maxpool2x2(h)
             if keep:
                 args[l] = a
     N = h.shape[0]
     flat = h.reshape(N, -1)
-    pre1 = fc(flat, fc_w[0], fc_b[0], relu=False)
-    z1 = np.maximum(pre1, 0.0)
-    pre2 = fc(z1, fc_w[1], fc_b[1], relu=False)
-    z2 = np.maximum(pre2, 0.0)
-    logits = fc(z2, fc_w[2], fc_b[2], relu=False)
+    pre1 = fc(flat, rd(fc_w[0]), fc_b[0], relu=False)
+    z1 = rd(np.maximum(pre1, 0.0))
+    pre2 = fc(z1, rd(fc_w[1]), fc_b[1], relu=False)
+    z2 = rd(np.maximum(pre2, 0.0))
+    logits = fc(z2, rd(fc_w[2]), fc_b[2], relu=False)
     out["logits"] = logits
     out["probs"] = softmax(logits)
     if keep:
@@ -228,7 +245,7 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
 
 
 def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: float = 0.0,
-                    pool_second_within: float = 0.0) -> Dict[str, object]:
+                    pool_second_within: float = 0.0, operand_round=None) -> Dict[str, object]:
     """Backward sweep from a kept forward pass ``f`` (vgg19_forward(keep=True)).
 
     With the defaults this is the gradient of the mean softmax cross-entropy:
@@ -245,7 +262,14 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     layer instead of 0 (t may be negative); with ``pool_second_within`` r > 0
     every pooling window whose two largest values differ by less than
     r * max(y) routes its gradient to the second of them instead of the first.
+
+    ``operand_round`` as in vgg19_forward (f must come from a forward pass with
+    the same setting): the gradient that enters the convolution stack and the
+    result of every data-gradient convolution are rounded, as are the
+    convolution weights the data gradient multiplies with; the dense layers'
+    backward products use the unrounded (master) weights and are not rounded.
     """
+    rd = operand_round if operand_round is not None else (lambda a: a)
     def relu_mask(pre, d):
         if mask_shift == 0.0:
             return np.where(pre > 0.0, d, 0.0)
@@ -259,7 +283,7 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     dfc_w[1], dfc_b[1], dz1 = fc_bwd(f["z1"], fc_w[1], dz2)
     dz1 = relu_mask(f["fc_pre"][0], dz1)
     dfc_w[0], dfc_b[0], dflat = fc_bwd(f["flat"], fc_w[0], dz1)
-    d = dflat.reshape(f["pool5"].shape)
+    d = rd(dflat.reshape(f["pool5"].shape))
     dconv_w = [None] * 16
     dconv_b = [None] * 16
     for l in range(15, -1, -1):
@@ -271,7 +295,7 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
         g = relu_mask(f["conv_pre"][l], d)
         dconv_w[l], dconv_b[l] = conv3x3_bwd_weight(f["conv_in"][l], g)
         if l > 0:
-            d = conv3x3_bwd_data(g, conv_w[l])
+            d = rd(conv3x3_bwd_data(g, rd(conv_w[l])))
     return dict(loss=loss, dconv_w=dconv_w, dconv_b=dconv_b, dfc_w=dfc_w, dfc_b=dfc_b)
 
 
@@ -306,15 +330,16 @@ def decision_margins(f: Dict[str, object]) -> Dict[str, float]:
     return {"relu": relu, "pool": pool}
 
 
-def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01) -> Dict[str, object]:
+def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01, operand_round=None) -> Dict[str, object]:
     """One step: forward, mean softmax cross-entropy, full backward, plain SGD.
 
     Returns loss, logits, probs, the 38 gradient tensors (dconv_w/dconv_b/
     dfc_w/dfc_b), the updated parameters (new_*) and the kept forward pass
-    (``fwd``) for vgg19_gradients / decision_margins.
+    (``fwd``) for vgg19_gradients / decision_margins.  With ``operand_round``
+    the update is applied to the unrounded (master) parameters.
     """
-    f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True)
-    res = vgg19_gradients(f, labels, conv_w, fc_w)
+    f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True, operand_round=operand_round)
+    res = vgg19_gradients(f, labels, conv_w, fc_w, operand_round=operand_round)
     res.update(logits=f["logits"], probs=f["probs"], fwd=f)
     res["new_conv_w"] = [sgd(conv_w[l], res["dconv_w"][l], lr) for l in range(16)]
     res["new_conv_b"] = [sgd(conv_b[l], res["dconv_b"][l], lr) for l in range(16)]

@@ -126,8 +126,12 @@ def _chk(rc: int, where: str):
         raise VggError(rc, where)
 
 
-def make_config(dtype: int, N: int, H: int, W: int, fc_hidden: int, classes: int, lr: float = 0.01) -> VggConfig:
-    return VggConfig(dtype, N, H, W, fc_hidden, classes, lr, 0)
+FLAG_FP32_MASTER = 1  # VGG_FLAG_FP32_MASTER
+
+
+def make_config(dtype: int, N: int, H: int, W: int, fc_hidden: int, classes: int, lr: float = 0.01,
+                flags: int = 0) -> VggConfig:
+    return VggConfig(dtype, N, H, W, fc_hidden, classes, lr, flags)
 
 
 def make_params(conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: Sequence) -> Vgg19Params:

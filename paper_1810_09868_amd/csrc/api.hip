@@ -25,13 +25,14 @@ int softmax_rows(int N, int K, const float *z, float *p, hipStream_t s);
 int softmax_xent_bwd(int N, int K, const float *p, const int32_t *labels, float *loss, float *dz, float *rowloss,
                      hipStream_t s);
 int sgd_update(size_t n, float *theta, const float *grad, float lr, hipStream_t s);
+int sgd_update_master(size_t n, float *theta, const float *grad, float lr, void *copy, int copy_dtype, hipStream_t s);
 int nchw_to_nhwc(int dtype, int N, int C, int H, int W, int Cpad, const float *x, void *y, hipStream_t s);
 int nhwc_to_nchw(int dtype, int N, int C, int H, int W, int Cpad, const void *x, float *y, hipStream_t s);
 int pad_channels(int dtype, size_t pixels, int C, int Cpad, const void *x, void *y, hipStream_t s);
 int convert(int sd, int dd, size_t n, const void *src, void *dst, hipStream_t s);
-int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s);
-int flip_packed_w(int CinP, int Cout, int CoutP, const float *src, float *dst, hipStream_t s);
-int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s);
+int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s, int colsP = 0);
+int flip_packed_w(int dst_dtype, int CinP, int Cout, int CoutP, const float *src, void *dst, hipStream_t s);
+int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s, int CinP = 0);
 int permute_fc_cols(int dst_dtype, int Out, int C, int HW, int to_hwc, const float *src, void *dst, hipStream_t s);
 size_t fc_workspace(int dtype, int N, int In, int Out);
 int fc_forward(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias, void *z, int z_dtype,
@@ -50,7 +51,8 @@ inline bool pool_after(int l) { return l == 1 || l == 3 || l == 7 || l == 11 || 
 bool cfg_ok(const vgg_config *c)
 {
     return c && dtype_ok(c->dtype) && c->N > 0 && c->H > 0 && c->W > 0 && c->H % 32 == 0 && c->W % 32 == 0 &&
-           c->fc_hidden > 0 && c->fc_hidden % 32 == 0 && c->classes > 0 && c->flags == 0 &&
+           c->fc_hidden > 0 && c->fc_hidden % 32 == 0 && c->classes > 0 &&
+           (c->flags == 0 || (c->flags == VGG_FLAG_FP32_MASTER && c->dtype == VGG_BF16)) &&
            (long)c->N * c->H * c->W <= (1L << 27);
 }
 
@@ -67,11 +69,13 @@ struct PackedLayout {
     size_t total;
 };
 
-PackedLayout packed_layout(const vgg_config *c)
+// master: the fp32 copy that a bf16 block with VGG_FLAG_FP32_MASTER carries behind it (same element
+// order inside every tensor, i.e. the bf16 channel padding).
+PackedLayout packed_layout(const vgg_config *c, bool master = false)
 {
     PackedLayout L;
     Bump b;
-    const int es = dtype_size(c->dtype);
+    const int es = master ? 4 : dtype_size(c->dtype);
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         L.cinp[l] = padded_channels(c->dtype, kConvCh[l][0]);
         L.conv_w[l] = b.take((size_t)9 * kConvCh[l][1] * L.cinp[l] * es);
@@ -88,6 +92,11 @@ PackedLayout packed_layout(const vgg_config *c)
     L.total = b.off;
     return L;
 }
+inline bool has_master(const vgg_config *c) { return c->dtype == VGG_BF16 && c->flags == VGG_FLAG_FP32_MASTER; }
+inline size_t packed_total(const vgg_config *c)
+{
+    return packed_layout(c).total + (has_master(c) ? packed_layout(c, true).total : 0);
+}
 
 // Workspace layout of the model-level calls.
 struct WsLayout {
@@ -99,6 +108,7 @@ struct WsLayout {
     size_t convpart;                   // partial sums of convolutions whose contraction is split
     // training only
     size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
+    size_t a32, dflat32;               // bf16 training: fp32 copies of a dense layer's input / of the flatten gradient
     size_t total;
     int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
 };
@@ -157,22 +167,28 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
     for (int l = 1; l < VGG19_NUM_CONV; ++l) {
         size_t s = conv3x3_igemm_workspace(c->dtype, c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
         if (s > cpart) cpart = s;
-        if (training) s = conv3x3_igemm_workspace(VGG_F32, c->N, L.H[l], L.W[l], kConvCh[l][1], kConvCh[l][0]);
+        if (training) s = conv3x3_igemm_workspace(c->dtype, c->N, L.H[l], L.W[l], kConvCh[l][1], kConvCh[l][0]);
         if (s > cpart) cpart = s;
     }
     L.convpart = b.take(cpart);
-    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = 0;
+    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = L.a32 = L.dflat32 = 0;
     if (training) {
         L.dlogits = b.take(N * c->classes * 4);
         L.dz2 = b.take(N * c->fc_hidden * 4);
         L.dz1 = b.take(N * c->fc_hidden * 4);
         L.gA = b.take(max_act);
         L.gB = b.take(max_act);
-        L.wflip = b.take((size_t)9 * 512 * 512 * 4);
-        L.grads = b.take(P.total);
+        L.wflip = b.take((size_t)9 * 512 * 512 * es);
+        const bool mixed = c->dtype == VGG_BF16;
+        L.grads = b.take(mixed ? packed_layout(c, true).total : P.total);
+        if (mixed) {
+            L.a32 = b.take(N * P.fc_in[0] * 4);
+            L.dflat32 = b.take(N * P.fc_in[0] * 4);
+        }
         size_t wg = 0, fb = 0;
         for (int l = 0; l < VGG19_NUM_CONV; ++l) {
-            const size_t s = conv3x3_wgrad_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
+            const size_t s = mixed ? conv3x3_wgrad_bf16_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1])
+                                   : conv3x3_wgrad_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
             if (s > wg) wg = s;
         }
         for (int l = 0; l < VGG19_NUM_FC; ++l) {
@@ -252,59 +268,96 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
 void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, const float *x, const int32_t *labels, char *pk,
                const vgg19_params *grads_out, float *loss, float *logits, char *ws, hipStream_t s, Recorder &rec)
 {
-    const int N = c->N;
+    const int N = c->N, dt = c->dtype;
+    // bf16: operands (activations, gradients with respect to activations, working weights) are bf16,
+    // sums fp32; the fp32 master parameters behind the bf16 block take the update.  The three dense
+    // layers' backward runs on the fp32 kernels, from the master weights and fp32 copies of its inputs.
+    const bool mixed = dt == VGG_BF16;
+    const PackedLayout Pm = mixed ? packed_layout(c, true) : P;
+    char *pm = mixed ? pk + P.total : pk;
     float *lg = logits ? logits : reinterpret_cast<float *>(ws + L.logits);
     float *pr = reinterpret_cast<float *>(ws + L.probs);
     run_forward(c, P, L, x, pk, lg, pr, true, ws, true, s, rec);
-    char *gr = ws + L.grads;  // gradient block, same layout as the packed parameters
+    char *gr = ws + L.grads;  // gradient block, same layout as the (master) parameters
     auto F = [](char *p) { return reinterpret_cast<float *>(p); };
     VGG_STEP(rec, K_OTHER, softmax_xent_bwd(N, c->classes, pr, labels, loss, F(ws + L.dlogits), F(ws + L.rowloss), s));
     // dense layers, last to first; each data gradient is masked by (input > 0)
     const char *fc_in[3] = {ws + L.pooled[15], ws + L.z1, ws + L.z2};
     float *fc_dz[3] = {F(ws + L.dz1), F(ws + L.dz2), F(ws + L.dlogits)};
-    float *dflat = F(ws + L.gA);
+    float *dflat = F(mixed ? ws + L.dflat32 : ws + L.gA);
     for (int l = 2; l >= 0; --l) {
         float *da = l == 0 ? dflat : fc_dz[l - 1];
+        const float *a = reinterpret_cast<const float *>(fc_in[l]);
+        if (mixed) {
+            VGG_STEP(rec, K_OTHER, convert(VGG_BF16, VGG_F32, (size_t)N * P.fc_in[l], fc_in[l], ws + L.a32, s));
+            a = F(ws + L.a32);
+        }
         if (!rec.skip(K_FCDW)) {
-            rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const float *>(fc_in[l]), F(pk + P.fc_w[l]),
-                                 fc_dz[l], F(gr + P.fc_w[l]), F(gr + P.fc_b[l]), da, 1, ws + L.fcbws, s);
+            rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], a, F(pm + Pm.fc_w[l]), fc_dz[l], F(gr + Pm.fc_w[l]),
+                                 F(gr + Pm.fc_b[l]), da, 1, ws + L.fcbws, s);
         }
         rec.skip(K_FCDA);  // issued by the same call; listed for the plan
     }
+    if (mixed) VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_BF16, (size_t)N * P.fc_in[0], dflat, ws + L.gA, s));
     // convolution stack, last to first
     char *gbuf[2] = {ws + L.gA, ws + L.gB};
     int cur = 0;  // gbuf[cur] holds the gradient w.r.t. the output of layer l (after its pool, if any)
     for (int l = VGG19_NUM_CONV - 1; l >= 0; --l) {
         const int H = L.H[l], W = L.W[l], Cin = kConvCh[l][0], Cout = kConvCh[l][1];
         if (pool_after(l)) {
-            VGG_STEP(rec, K_POOLB, maxpool2x2_bwd(VGG_F32, N, H, W, Cout, gbuf[cur],
+            VGG_STEP(rec, K_POOLB, maxpool2x2_bwd(dt, N, H, W, Cout, gbuf[cur],
                                                   reinterpret_cast<const uint8_t *>(ws + L.argmax[l]), gbuf[cur ^ 1], s));
             cur ^= 1;
         }
         const char *xin = l == 0 ? ws + L.x0 : (pool_after(l - 1) ? ws + L.pooled[l - 1] : ws + L.act[l - 1]);
-        VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin), F(gbuf[cur]),
-                                            F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
+        if (mixed)
+            VGG_STEP(rec, K_WGRAD, conv3x3_wgrad_bf16(N, H, W, P.cinp[l], Cout, reinterpret_cast<const bf16_t *>(xin),
+                                                     reinterpret_cast<const bf16_t *>(gbuf[cur]), F(gr + Pm.conv_w[l]),
+                                                     F(gr + Pm.conv_b[l]), ws + L.wgws, s));
+        else
+            VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin),
+                                                F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
         if (l > 0) {
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
-            VGG_STEP(rec, K_OTHER, flip_packed_w(P.cinp[l], Cout, Cout, F(pk + P.conv_w[l]), F(ws + L.wflip), s));
-            VGG_STEP(rec, K_DGRAD, conv3x3_igemm(VGG_F32, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
+            VGG_STEP(rec, K_OTHER, flip_packed_w(dt, P.cinp[l], Cout, Cout, F(pm + Pm.conv_w[l]), ws + L.wflip, s));
+            VGG_STEP(rec, K_DGRAD, conv3x3_igemm(dt, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
                                                 gbuf[cur ^ 1], nullptr, 0, ws + L.convpart, s));
             cur ^= 1;
         }
     }
     if (grads_out) {
         for (int l = 0; l < VGG19_NUM_CONV; ++l) {
-            VGG_STEP(rec, K_OTHER, unpack_conv_w(kConvCh[l][0], kConvCh[l][1], F(gr + P.conv_w[l]), grads_out->conv_w[l], s));
-            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, kConvCh[l][1], gr + P.conv_b[l], grads_out->conv_b[l], s));
+            VGG_STEP(rec, K_OTHER, unpack_conv_w(kConvCh[l][0], kConvCh[l][1], F(gr + Pm.conv_w[l]), grads_out->conv_w[l], s,
+                                                 Pm.cinp[l]));
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, kConvCh[l][1], gr + Pm.conv_b[l], grads_out->conv_b[l], s));
         }
-        VGG_STEP(rec, K_OTHER, permute_fc_cols(VGG_F32, P.fc_out[0], 512, P.fc_in[0] / 512, 0, F(gr + P.fc_w[0]),
+        VGG_STEP(rec, K_OTHER, permute_fc_cols(VGG_F32, P.fc_out[0], 512, P.fc_in[0] / 512, 0, F(gr + Pm.fc_w[0]),
                                                grads_out->fc_w[0], s));
         for (int l = 1; l < VGG19_NUM_FC; ++l)
-            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, (size_t)P.fc_in[l] * P.fc_out[l], gr + P.fc_w[l], grads_out->fc_w[l], s));
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, (size_t)P.fc_in[l] * P.fc_out[l], gr + Pm.fc_w[l], grads_out->fc_w[l], s));
         for (int l = 0; l < VGG19_NUM_FC; ++l)
-            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], gr + P.fc_b[l], grads_out->fc_b[l], s));
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], gr + Pm.fc_b[l], grads_out->fc_b[l], s));
     }
-    VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
+    if (!mixed) {
+        VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
+        return;
+    }
+    // master <- master - lr * gradient, working copy <- master (bf16 weights, fp32 biases), tensor by tensor
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+        VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)9 * kConvCh[l][1] * P.cinp[l], F(pm + Pm.conv_w[l]), F(gr + Pm.conv_w[l]),
+                                                 c->lr, pk + P.conv_w[l], VGG_BF16, s));
+        VGG_STEP(rec, K_OTHER, sgd_update_master(kConvCh[l][1], F(pm + Pm.conv_b[l]), F(gr + Pm.conv_b[l]), c->lr,
+                                                 pk + P.conv_b[l], VGG_F32, s));
+    }
+    for (int l = 0; l < VGG19_NUM_FC; ++l) {
+        VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)P.fc_in[l] * P.fc_out[l], F(pm + Pm.fc_w[l]), F(gr + Pm.fc_w[l]), c->lr,
+                                                 pk + P.fc_w[l], VGG_BF16, s));
+    }
+    // (bias counts need not be multiples of four: the dense biases take the plain kernels)
+    for (int l = 0; l < VGG19_NUM_FC; ++l) {
+        VGG_STEP(rec, K_OTHER, sgd_update(P.fc_out[l], F(pm + Pm.fc_b[l]), F(gr + Pm.fc_b[l]), c->lr, s));
+        VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], pm + Pm.fc_b[l], pk + P.fc_b[l], s));
+    }
 }
 
 bool params_ok(const vgg19_params *p)
@@ -599,7 +652,7 @@ int vgg_sgd_update(size_t n, float *theta, const float *grad, float lr, void *st
     return sgd_update(n, theta, grad, lr, (hipStream_t)stream);
 }
 
-size_t vgg19_packed_bytes(const vgg_config *cfg) { return cfg_ok(cfg) ? packed_layout(cfg).total : 0; }
+size_t vgg19_packed_bytes(const vgg_config *cfg) { return cfg_ok(cfg) ? packed_total(cfg) : 0; }
 
 size_t vgg19_forward_workspace_bytes(const vgg_config *cfg)
 {
@@ -609,7 +662,7 @@ size_t vgg19_forward_workspace_bytes(const vgg_config *cfg)
 
 size_t vgg19_train_workspace_bytes(const vgg_config *cfg)
 {
-    if (!cfg_ok(cfg) || cfg->dtype != VGG_F32) return 0;
+    if (!cfg_ok(cfg) || (cfg->dtype != VGG_F32 && !has_master(cfg))) return 0;
     return ws_layout(cfg, packed_layout(cfg), true).total;
 }
 
@@ -620,19 +673,23 @@ int vgg19_pack_params(const vgg_config *cfg, const vgg19_params *canon, void *pa
     if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
     if (!params_ok(canon)) return VGG_ERR_NULL;
     if (!aligned16(packed) || !params_aligned(canon)) return VGG_ERR_ALIGN;
-    const PackedLayout P = packed_layout(cfg);
-    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    if (packed_bytes < packed_total(cfg)) return VGG_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    char *pk = static_cast<char *>(packed);
     int rc = VGG_OK;
-    for (int l = 0; l < VGG19_NUM_CONV && !rc; ++l) {
-        rc = pack_conv_w(cfg->dtype, kConvCh[l][0], kConvCh[l][1], canon->conv_w[l], pk + P.conv_w[l], 0, s);
-        if (!rc) rc = convert(VGG_F32, VGG_F32, kConvCh[l][1], canon->conv_b[l], pk + P.conv_b[l], s);
+    // the block in cfg->dtype, then (bf16 with fp32 master) the same tensors in fp32 behind it
+    for (int pass = 0; pass < (has_master(cfg) ? 2 : 1) && !rc; ++pass) {
+        const PackedLayout P = packed_layout(cfg, pass == 1);
+        const int dt = pass == 1 ? VGG_F32 : cfg->dtype;
+        char *pk = static_cast<char *>(packed) + (pass == 1 ? packed_layout(cfg).total : 0);
+        for (int l = 0; l < VGG19_NUM_CONV && !rc; ++l) {
+            rc = pack_conv_w(dt, kConvCh[l][0], kConvCh[l][1], canon->conv_w[l], pk + P.conv_w[l], 0, s, P.cinp[l]);
+            if (!rc) rc = convert(VGG_F32, VGG_F32, kConvCh[l][1], canon->conv_b[l], pk + P.conv_b[l], s);
+        }
+        if (!rc) rc = permute_fc_cols(dt, P.fc_out[0], 512, P.fc_in[0] / 512, 1, canon->fc_w[0], pk + P.fc_w[0], s);
+        for (int l = 1; l < VGG19_NUM_FC && !rc; ++l)
+            rc = convert(VGG_F32, dt, (size_t)P.fc_in[l] * P.fc_out[l], canon->fc_w[l], pk + P.fc_w[l], s);
+        for (int l = 0; l < VGG19_NUM_FC && !rc; ++l) rc = convert(VGG_F32, VGG_F32, P.fc_out[l], canon->fc_b[l], pk + P.fc_b[l], s);
     }
-    if (!rc) rc = permute_fc_cols(cfg->dtype, P.fc_out[0], 512, P.fc_in[0] / 512, 1, canon->fc_w[0], pk + P.fc_w[0], s);
-    for (int l = 1; l < VGG19_NUM_FC && !rc; ++l)
-        rc = convert(VGG_F32, cfg->dtype, (size_t)P.fc_in[l] * P.fc_out[l], canon->fc_w[l], pk + P.fc_w[l], s);
-    for (int l = 0; l < VGG19_NUM_FC && !rc; ++l) rc = convert(VGG_F32, VGG_F32, P.fc_out[l], canon->fc_b[l], pk + P.fc_b[l], s);
     return rc;
 }
 
@@ -640,17 +697,19 @@ int vgg19_unpack_params(const vgg_config *cfg, const void *packed, size_t packed
 {
     if (!cfg || !out || !packed) return VGG_ERR_NULL;
     if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
-    if (cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
     if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (cfg->dtype != VGG_F32 && !has_master(cfg)) return VGG_ERR_UNSUPPORTED;
     if (!params_ok(out)) return VGG_ERR_NULL;
     if (!aligned16(packed) || !params_aligned(out)) return VGG_ERR_ALIGN;
-    const PackedLayout P = packed_layout(cfg);
-    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    if (packed_bytes < packed_total(cfg)) return VGG_ERR_WORKSPACE;
+    // (bf16 with fp32 master: the master copy is what is read back)
+    const PackedLayout P = packed_layout(cfg, has_master(cfg));
     hipStream_t s = (hipStream_t)stream;
-    const char *pk = static_cast<const char *>(packed);
+    const char *pk = static_cast<const char *>(packed) + (has_master(cfg) ? packed_layout(cfg).total : 0);
     int rc = VGG_OK;
     for (int l = 0; l < VGG19_NUM_CONV && !rc; ++l) {
-        rc = unpack_conv_w(kConvCh[l][0], kConvCh[l][1], reinterpret_cast<const float *>(pk + P.conv_w[l]), out->conv_w[l], s);
+        rc = unpack_conv_w(kConvCh[l][0], kConvCh[l][1], reinterpret_cast<const float *>(pk + P.conv_w[l]), out->conv_w[l], s,
+                           P.cinp[l]);
         if (!rc) rc = convert(VGG_F32, VGG_F32, kConvCh[l][1], pk + P.conv_b[l], out->conv_b[l], s);
     }
     if (!rc)
@@ -685,14 +744,14 @@ int vgg19_train_step(const vgg_config *cfg, const float *x, const int32_t *label
 {
     if (!cfg || !x || !labels || !packed) return VGG_ERR_NULL;
     if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
-    if (cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
     if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
+    if (cfg->dtype != VGG_F32 && !has_master(cfg)) return VGG_ERR_UNSUPPORTED;
     if (grads && !params_ok(grads)) return VGG_ERR_NULL;
     if (!aligned16(x) || !aligned16(packed) || (logits && !aligned16(logits)) || (ws && !aligned16(ws)) ||
         (grads && !params_aligned(grads)))
         return VGG_ERR_ALIGN;
     const PackedLayout P = packed_layout(cfg);
-    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    if (packed_bytes < packed_total(cfg)) return VGG_ERR_WORKSPACE;
     const WsLayout L = ws_layout(cfg, P, true);
     if (!ws || ws_bytes < L.total) return VGG_ERR_WORKSPACE;
     Recorder rec{nullptr, 0, 0, false, VGG_OK};
@@ -707,11 +766,11 @@ int vgg19_timed(const vgg_config *cfg, int training, const float *x, const int32
 {
     if (!cfg || !x || !packed || !kinds_host || !ms_host || (training && !labels)) return VGG_ERR_NULL;
     if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
-    if (training && cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
     if (!cfg_ok(cfg) || cap <= 0) return VGG_ERR_SHAPE;
+    if (training && cfg->dtype != VGG_F32 && !has_master(cfg)) return VGG_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(packed) || (logits && !aligned16(logits)) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
     const PackedLayout P = packed_layout(cfg);
-    if (packed_bytes < P.total) return VGG_ERR_WORKSPACE;
+    if (packed_bytes < (training ? packed_total(cfg) : P.total)) return VGG_ERR_WORKSPACE;
     const WsLayout L = ws_layout(cfg, P, training != 0);
     if (!ws || ws_bytes < L.total) return VGG_ERR_WORKSPACE;
     const int need = vgg19_plan(cfg, training, nullptr, 0);
@@ -748,7 +807,7 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap)
     if (!cfg) return VGG_ERR_NULL;
     if (!dtype_ok(cfg->dtype)) return VGG_ERR_DTYPE;
     if (!cfg_ok(cfg)) return VGG_ERR_SHAPE;
-    if (training && cfg->dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
+    if (training && cfg->dtype != VGG_F32 && !has_master(cfg)) return VGG_ERR_UNSUPPORTED;
     const PackedLayout P = packed_layout(cfg);
     const WsLayout L = ws_layout(cfg, P, training != 0);
     Recorder rec{kinds_host, kinds_host ? cap : 0, 0, true, VGG_OK};

@@ -176,6 +176,33 @@ int sgd_update(size_t n, float *theta, const float *grad, float lr, hipStream_t 
     return launch_status();
 }
 
+// Mixed precision: the fp32 master value takes the step and the working copy (bf16 weights, fp32
+// biases) is refreshed from it in the same pass.  n must be a multiple of 4.
+template <typename TC>
+__global__ void sgd_master_kernel(float *__restrict__ theta, const float *__restrict__ grad, float lr, TC *__restrict__ copy,
+                                  size_t n4)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    f32x4 t = reinterpret_cast<f32x4 *>(theta)[i];
+    const f32x4 g = reinterpret_cast<const f32x4 *>(grad)[i];
+    t.x -= lr * g.x; t.y -= lr * g.y; t.z -= lr * g.z; t.w -= lr * g.w;
+    reinterpret_cast<f32x4 *>(theta)[i] = t;
+    store4(copy + i * 4, t.x, t.y, t.z, t.w);
+}
+
+int sgd_update_master(size_t n, float *theta, const float *grad, float lr, void *copy, int copy_dtype, hipStream_t s)
+{
+    if (n % 4) return VGG_ERR_UNSUPPORTED;
+    const size_t n4 = n / 4;
+    const dim3 grid((unsigned)((n4 + 255) / 256));
+    if (copy_dtype == VGG_BF16)
+        hipLaunchKernelGGL(sgd_master_kernel<bf16_t>, grid, dim3(256), 0, s, theta, grad, lr, (bf16_t *)copy, n4);
+    else
+        hipLaunchKernelGGL(sgd_master_kernel<float>, grid, dim3(256), 0, s, theta, grad, lr, (float *)copy, n4);
+    return launch_status();
+}
+
 // ------------------------------------------------------- layout transforms
 // NCHW fp32 -> NHWC T with zero padding of the channels up to Cpad.  One
 // thread per output pixel; reads are coalesced along w for each channel.
@@ -300,10 +327,11 @@ __global__ void pack_conv_w_kernel(const float *__restrict__ w, T *__restrict__ 
     Elem<T>::store(dst + idx, v);
 }
 
-int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s)
+// colsP: padded length of the contiguous dimension (0: the granularity of dtype)
+int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s, int colsP = 0)
 {
     const int rows = flip ? Cin : Cout;
-    const int colsP = padded_channels(dtype, flip ? Cout : Cin);
+    if (colsP == 0) colsP = padded_channels(dtype, flip ? Cout : Cin);
     const size_t total = (size_t)9 * rows * colsP;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (dtype == VGG_BF16)
@@ -315,7 +343,8 @@ int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int fli
 
 // Packed-forward fp32 [9][Cout][CinP] -> the flipped operand [9][Cin'][CoutP] where
 // Cin' = CinP rows are kept (padding rows are zero anyway).
-__global__ void flip_packed_w_kernel(const float *__restrict__ src, float *__restrict__ dst, int CinP, int Cout, int CoutP)
+template <typename TD>
+__global__ void flip_packed_w_kernel(const float *__restrict__ src, TD *__restrict__ dst, int CinP, int Cout, int CoutP)
 {
     const size_t total = (size_t)9 * CinP * CoutP;
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -323,13 +352,17 @@ __global__ void flip_packed_w_kernel(const float *__restrict__ src, float *__res
     const int co = (int)(idx % CoutP);
     const int ci = (int)((idx / CoutP) % CinP);
     const int t = (int)(idx / ((size_t)CoutP * CinP));
-    dst[idx] = co < Cout ? src[((size_t)(8 - t) * Cout + co) * CinP + ci] : 0.f;
+    Elem<TD>::store(dst + idx, co < Cout ? src[((size_t)(8 - t) * Cout + co) * CinP + ci] : 0.f);
 }
 
-int flip_packed_w(int CinP, int Cout, int CoutP, const float *src, float *dst, hipStream_t s)
+int flip_packed_w(int dst_dtype, int CinP, int Cout, int CoutP, const float *src, void *dst, hipStream_t s)
 {
     const size_t total = (size_t)9 * CinP * CoutP;
-    hipLaunchKernelGGL(flip_packed_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, src, dst, CinP, Cout, CoutP);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (dst_dtype == VGG_BF16)
+        hipLaunchKernelGGL(flip_packed_w_kernel<bf16_t>, grid, dim3(256), 0, s, src, (bf16_t *)dst, CinP, Cout, CoutP);
+    else
+        hipLaunchKernelGGL(flip_packed_w_kernel<float>, grid, dim3(256), 0, s, src, (float *)dst, CinP, Cout, CoutP);
     return launch_status();
 }
 
@@ -344,11 +377,12 @@ __global__ void unpack_conv_w_kernel(const float *__restrict__ src, float *__res
     w[idx] = src[((size_t)t * Cout + co) * CinP + ci];
 }
 
-int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s)
+// CinP: channel stride of src (0: the fp32 granularity)
+int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s, int CinP = 0)
 {
     const size_t total = (size_t)Cout * Cin * 9;
     hipLaunchKernelGGL(unpack_conv_w_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, src, w, Cin, Cout,
-                       padded_channels(VGG_F32, Cin));
+                       CinP ? CinP : padded_channels(VGG_F32, Cin));
     return launch_status();
 }
 

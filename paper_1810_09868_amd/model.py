@@ -21,7 +21,9 @@ class Vgg19:
                  training: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("Vgg19 needs a GPU: the HIP library is the only implementation")
-        self.cfg = B.make_config(dtype, N, H, W, fc_hidden, classes, lr)
+        # bf16 training keeps fp32 master parameters behind the bf16 ones
+        flags = B.FLAG_FP32_MASTER if (training and dtype == B.BF16) else 0
+        self.cfg = B.make_config(dtype, N, H, W, fc_hidden, classes, lr, flags)
         self.training = training
         nb = B.vgg19_packed_bytes(self.cfg)
         if nb == 0:

@@ -27,17 +27,18 @@ def _f64(lst):
 BAND = 2e-5
 
 
-def _gradient_check(g, ref, inp, tol):
+def _gradient_check(g, ref, inp, tol, rd=None):
     """Every gradient tensor within tol of the oracle's, plus twice the spread of the oracle's own
     gradient when the decisions inside BAND are taken the other way.  A tensor that no ambiguous
     decision reaches (always the last dense layer; every tensor when there is none) has zero spread
     and is held to tol alone."""
     keys = (("conv_w", "dconv_w"), ("conv_b", "dconv_b"), ("fc_w", "dfc_w"), ("fc_b", "dfc_b"))
     f = ref["fwd"]
-    alts = [R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), mask_shift=+BAND),
-            R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), mask_shift=-BAND)]
+    alts = [R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), mask_shift=+BAND, operand_round=rd),
+            R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), mask_shift=-BAND, operand_round=rd)]
     if R.decision_margins(f)["pool"] < BAND:
-        alts.append(R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), pool_second_within=BAND))
+        alts.append(R.vgg19_gradients(f, inp.labels, _f64(inp.conv_w), _f64(inp.fc_w), pool_second_within=BAND,
+                                      operand_round=rd))
     worst = 0.0
     spread = {}
     for k, rk in keys:
@@ -111,6 +112,136 @@ def test_tiny_vgg19_train_step_fp32():
             assert np.abs(upd - want).max() <= 2e-7 * np.abs(before[k][l]).max() + 1e-6 * np.abs(want).max(), (k, l)
 
 
+def _bf16_train_step_vs_oracle(inp, N, H, W, hidden, classes):
+    """bf16 training step against the oracle run with bfloat16 operands (the accelerator's matrix-unit
+    precision).  Rounding to 8 bits after every layer is a chaotic quantiser: two correct
+    implementations that sum in a different order disagree by one bf16 step on some activations after
+    the first layer and, nineteen layers on, take different ReLU and pooling decisions on a fraction of
+    a percent of the units.  Loss, logits and the last dense layer's gradient (which no decision
+    reaches) are held to the bf16 tolerance; every other gradient tensor can only be held to an
+    aggregate bound here (wrong wiring gives a relative L2 error near or above 1), and the per-layer
+    kernels are held to the tolerance on the oracle's own tensors in the test below."""
+    ref = R.vgg19_train_step(inp.x, inp.labels, _f64(inp.conv_w), _f64(inp.conv_b), _f64(inp.fc_w), _f64(inp.fc_b),
+                             lr=0.01, operand_round=R.round_bf16)
+    m = Vgg19(B.BF16, N, H, W, hidden, classes, lr=0.01, training=True)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    before = m.unpack()
+    for k, src in (("conv_w", inp.conv_w), ("conv_b", inp.conv_b), ("fc_w", inp.fc_w), ("fc_b", inp.fc_b)):
+        for a, b in zip(before[k], src):
+            assert np.array_equal(a, b)                    # the fp32 master copy is what unpack returns
+    g = m.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
+    torch.cuda.synchronize()
+    tol = TOL[B.BF16]
+    assert abs(m.loss.item() - ref["loss"]) <= tol * abs(ref["loss"])
+    assert max_rel_err(m.logits.cpu().numpy(), ref["logits"]) <= tol
+    assert max_rel_err(g["fc_w"][2].cpu().numpy(), ref["dfc_w"][2]) <= tol
+    assert max_rel_err(g["fc_b"][2].cpu().numpy(), ref["dfc_b"][2]) <= tol
+    worst = 0.0
+    for k, rk in (("conv_w", "dconv_w"), ("conv_b", "dconv_b"), ("fc_w", "dfc_w"), ("fc_b", "dfc_b")):
+        for l, (a, b) in enumerate(zip(g[k], ref[rk])):
+            e = np.linalg.norm(a.cpu().numpy().astype(np.float64) - b) / np.linalg.norm(b)
+            worst = max(worst, e)
+            assert e <= 0.4, (k, l, e)
+    print("worst relative L2 gradient error", worst)
+    after = m.unpack()
+    for k in ("conv_w", "conv_b", "fc_w", "fc_b"):
+        for l, a in enumerate(after[k]):
+            # the master parameters moved by -lr * (the gradient the step reported), to fp32 rounding
+            upd = a.astype(np.float64) - before[k][l].astype(np.float64)
+            want = -0.01 * g[k][l].cpu().numpy().astype(np.float64)
+            assert np.abs(upd - want).max() <= 2e-7 * np.abs(before[k][l]).max() + 1e-6 * np.abs(want).max(), (k, l)
+    # the bf16 parameters the next forward pass reads are the rounded new master parameters: packing the
+    # master values afresh gives the same working block, bit for bit
+    m2 = Vgg19(B.BF16, N, H, W, hidden, classes)
+    m2.pack(after["conv_w"], after["conv_b"], after["fc_w"], after["fc_b"])
+    nb = m2.packed.numel()
+    assert torch.equal(m.packed[:nb], m2.packed)
+
+
+def _bf16_backward_kernels_on_oracle_tensors(inp):
+    """Every convolution layer's bf16 weight- and data-gradient launch, and every pool's backward, on
+    the tensors of the oracle's own bf16-operand pass (inputs from the oracle, so both sides start
+    from identical values and no decision is left to rounding): held to the bf16 tolerance."""
+    rd = R.round_bf16
+    cw = _f64(inp.conv_w)
+    f = R.vgg19_forward(inp.x, cw, _f64(inp.conv_b), _f64(inp.fc_w), _f64(inp.fc_b), keep=True, operand_round=rd)
+    _, dlogits = R.softmax_xent(f["probs"], inp.labels)
+    _, _, dz2 = R.fc_bwd(f["z2"], inp.fc_w[2], dlogits)
+    dz2 = np.where(f["fc_pre"][1] > 0, dz2, 0.0)
+    _, _, dz1 = R.fc_bwd(f["z1"], inp.fc_w[1], dz2)
+    dz1 = np.where(f["fc_pre"][0] > 0, dz1, 0.0)
+    _, _, dflat = R.fc_bwd(f["flat"], inp.fc_w[0], dz1)
+    d = rd(dflat.reshape(f["pool5"].shape))
+    tol = TOL[B.BF16]
+    worst = 0.0
+    for l in range(15, -1, -1):
+        x = f["conv_in"][l]
+        N, Cin, H, W = x.shape
+        Cout = cw[l].shape[0]
+        if l in (1, 3, 7, 11, 15):
+            arg = f["pool_arg"][l]
+            want = R.maxpool2x2_bwd(d, arg)
+            dy = to_nhwc(d, B.BF16)
+            a = torch.from_numpy(np.ascontiguousarray(arg.transpose(0, 2, 3, 1))).cuda()
+            dx = torch.empty((N, H, W, Cout), dtype=torch.bfloat16, device="cuda")
+            B.vgg_maxpool2x2_bwd(B.BF16, N, H, W, Cout, dy, a, dx)
+            torch.cuda.synchronize()
+            assert np.array_equal(from_nhwc(dx), want), l      # routing only: exact
+            d = want
+        gmask = np.where(f["conv_pre"][l] > 0, d, 0.0)         # bf16 values
+        dw_ref, db_ref = R.conv3x3_bwd_weight(x, gmask)
+        xg, gg = to_nhwc(x, B.BF16), to_nhwc(gmask, B.BF16)
+        cp = B.vgg_padded_channels(B.BF16, Cin)
+        dwp = torch.empty((9, Cout, cp), device="cuda")
+        db = torch.empty((Cout,), device="cuda")
+        ws = ws_bytes(B.vgg_conv3x3_bwd_weight_workspace_bytes(B.BF16, N, H, W, Cin, Cout))
+        B.vgg_conv3x3_bwd_weight(B.BF16, N, H, W, Cin, Cout, xg, gg, dwp, db, ws)
+        torch.cuda.synchronize()
+        dw = dwp[:, :, :Cin].reshape(3, 3, Cout, Cin).permute(2, 3, 0, 1).cpu().numpy()
+        e = max(max_rel_err(dw, dw_ref), max_rel_err(db.cpu().numpy(), db_ref))
+        worst = max(worst, e)
+        assert e <= tol, ("weight gradient", l, e)
+        if l == 0:
+            break
+        want = rd(R.conv3x3_bwd_data(gmask, rd(cw[l])))
+        wtf = torch.empty((9, Cin, B.vgg_padded_channels(B.BF16, Cout)), dtype=torch.bfloat16, device="cuda")
+        B.vgg_conv_pack_weights(B.BF16, Cin, Cout, dev(inp.conv_w[l]), wtf, 1)
+        dxg = torch.empty((N, H, W, Cin), dtype=torch.bfloat16, device="cuda")
+        ws = ws_bytes(B.vgg_conv3x3_bwd_data_workspace_bytes(B.BF16, N, H, W, Cin, Cout))
+        B.vgg_conv3x3_bwd_data(B.BF16, N, H, W, Cin, Cout, gg, wtf, xg, dxg, ws)
+        torch.cuda.synchronize()
+        e = max_rel_err(from_nhwc(dxg), want * (x > 0))
+        worst = max(worst, e)
+        assert e <= tol, ("data gradient", l, e)
+        d = want                                               # (the next layer's mask is applied to it there)
+    return worst
+
+
+def test_tiny_vgg19_train_step_bf16():
+    _bf16_train_step_vs_oracle(synth.tiny_config(seed=0), 2, 32, 32, 512, 10)
+
+
+def test_full_vgg19_train_step_bf16_224_vs_oracle_batch2():
+    _bf16_train_step_vs_oracle(synth.vgg19_inputs(2, 224, 224, 4096, 1000, seed=1), 2, 224, 224, 4096, 1000)
+
+
+def test_bf16_backward_kernels_on_oracle_tensors_tiny():
+    print("worst error", _bf16_backward_kernels_on_oracle_tensors(synth.tiny_config(seed=0)))
+
+
+def test_bf16_backward_kernels_on_oracle_tensors_224():
+    print("worst error", _bf16_backward_kernels_on_oracle_tensors(synth.vgg19_inputs(2, 224, 224, 4096, 1000, seed=1)))
+
+
+def test_bf16_training_needs_the_master_copy():
+    cfg = B.make_config(B.BF16, 2, 32, 32, 512, 10, 0.01)          # no master copy
+    assert B.vgg19_train_workspace_bytes(cfg) == 0
+    cfgm = B.make_config(B.BF16, 2, 32, 32, 512, 10, 0.01, B.FLAG_FP32_MASTER)
+    assert B.vgg19_train_workspace_bytes(cfgm) > 0
+    assert B.vgg19_packed_bytes(cfgm) > 3 * B.vgg19_packed_bytes(cfg) - 4096 * 38    # bf16 + fp32 copy (biases fp32 in both)
+    assert B.vgg19_packed_bytes(B.make_config(B.F32, 2, 32, 32, 512, 10, 0.01, B.FLAG_FP32_MASTER)) == 0   # bf16 only
+
+
 def test_conv_microbenchmark_shape_sampled_images():
     # 128 -> 256 channels, 56x56, batch 100 on the GPU; the oracle recomputes three of the images
     N, H, W, Cin, Cout = 100, 56, 56, 128, 256
@@ -181,16 +312,18 @@ def test_full_vgg19_train_step_224_vs_oracle_batch2():
     _updated_params_check(m.unpack(), ref, spread, tol, 0.01)
 
 
-def test_full_vgg19_train_step_batch100_is_mean_of_chunks():
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_full_vgg19_train_step_batch100_is_mean_of_chunks(dtype):
     # The loss is a mean over images, so the batch-100 gradient equals the mean of the gradients of
     # five batch-20 steps from the same parameters (a property that holds at any size); the batch-2
     # test above ties the same kernels at the same spatial sizes to the oracle.  The chunks must run
     # the same arithmetic per image as the full batch: a ReLU or pooling decision that rounding
     # flips moves a gradient by far more than the tolerance.  Halves do (below roughly 40 images
     # the 14x14 layers split their contraction over several workgroups, another summation order).
+    # bf16: the forward pass and the data gradients are then bit-identical per image, so the same holds.
     N, chunk = 100, 50
     inp = synth.full_config(N, seed=2)
-    big = Vgg19(B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
+    big = Vgg19(dtype, N, 224, 224, 4096, 1000, lr=0.01, training=True)
     big.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
     gb = big.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
     torch.cuda.synchronize()
@@ -200,7 +333,7 @@ def test_full_vgg19_train_step_batch100_is_mean_of_chunks():
     new_big = big.unpack()
     del big
     torch.cuda.empty_cache()
-    small = Vgg19(B.F32, chunk, 224, 224, 4096, 1000, lr=0.01, training=True)
+    small = Vgg19(dtype, chunk, 224, 224, 4096, 1000, lr=0.01, training=True)
     acc = None
     losses = []
     for c in range(N // chunk):

@@ -388,3 +388,55 @@ def test_tiny_vgg19_forward_properties_and_train_step_fd():
         idx = np.unravel_index(np.argmax(np.abs(g)), g.shape)
         fd = (loss_with(kind, l, idx, h) - loss_with(kind, l, idx, -h)) / (2 * h)
         assert abs(fd - g[idx]) < 2e-5 * max(abs(g[idx]), 1e-3), (kind, l, idx, fd, g[idx])
+
+
+def test_round_bf16_closed_forms_and_library_conversion():
+    # bfloat16 keeps 8 significant bits (format definition): representable values are fixed points,
+    # halves go to the even neighbour, everything else to the nearest
+    rep = np.array([0.0, 1.0, -1.0, 0.5, 1.5, 255.0, 1.0 + 2.0 ** -7, -3.0 * 2.0 ** -20, 2.0 ** 100])
+    assert np.array_equal(R.round_bf16(rep), rep)
+    ulp = 2.0 ** -7                                             # spacing in [1, 2)
+    assert R.round_bf16(np.array([1.0 + 0.5 * ulp]))[0] == 1.0                 # tie -> even (mantissa 0)
+    assert R.round_bf16(np.array([1.0 + 1.5 * ulp]))[0] == 1.0 + 2.0 * ulp     # tie -> even (mantissa 2)
+    assert R.round_bf16(np.array([1.0 + 0.49 * ulp]))[0] == 1.0
+    assert R.round_bf16(np.array([1.0 + 0.51 * ulp]))[0] == 1.0 + ulp
+    assert R.round_bf16(np.array([-(1.0 + 0.51 * ulp)]))[0] == -(1.0 + ulp)
+    assert R.round_bf16(np.array([2.0 - 0.25 * ulp]))[0] == 2.0                # rounds up into the next binade
+    # an independent conversion routine on random float32 values
+    import torch
+    rng = np.random.default_rng(5)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(R.round_bf16(v), want)
+    r = R.round_bf16(v)
+    assert np.all(np.abs(r - v) <= np.abs(v) * 2.0 ** -8)        # relative error bound of 8 significant bits
+    assert np.array_equal(R.round_bf16(r), r)                    # idempotent
+
+
+def test_rounded_operand_model_reduces_to_plain_model_on_representable_data():
+    # With every operand already a bfloat16 value only the rounding of layer outputs differs from the
+    # plain model; with an identity "rounding" nothing does.  Pins that operand_round touches no sums.
+    from paper_1810_09868_amd import synth
+    inp = synth.tiny_config(seed=4)
+    f64 = lambda lst: [a.astype(np.float64) for a in lst]
+    plain = R.vgg19_train_step(inp.x, inp.labels, f64(inp.conv_w), f64(inp.conv_b), f64(inp.fc_w), f64(inp.fc_b), lr=0.01)
+    ident = R.vgg19_train_step(inp.x, inp.labels, f64(inp.conv_w), f64(inp.conv_b), f64(inp.fc_w), f64(inp.fc_b), lr=0.01,
+                               operand_round=lambda a: a)
+    assert np.array_equal(plain["logits"], ident["logits"])
+    for k in ("dconv_w", "dfc_w", "new_conv_w", "new_fc_b"):
+        for a, b in zip(plain[k], ident[k]):
+            assert np.array_equal(a, b)
+    # bfloat16 operands: every product operand the model kept is a fixed point of the rounding, the
+    # result stays within the format's error of the plain model, and the update moves the unrounded parameters
+    rb = R.vgg19_train_step(inp.x, inp.labels, f64(inp.conv_w), f64(inp.conv_b), f64(inp.fc_w), f64(inp.fc_b), lr=0.01,
+                            operand_round=R.round_bf16)
+    f = rb["fwd"]
+    for a in list(f["conv_in"]) + list(f["conv_out"]) + [f["z1"], f["z2"], f["flat"]]:
+        assert np.array_equal(R.round_bf16(a), a)
+    assert not np.array_equal(R.round_bf16(f["logits"]), f["logits"])
+    scale = np.abs(plain["logits"]).max()
+    err = np.abs(rb["logits"] - plain["logits"]).max() / scale
+    assert 1e-5 < err < 2e-2
+    for l in range(16):
+        upd = rb["new_conv_w"][l] - inp.conv_w[l].astype(np.float64)
+        np.testing.assert_allclose(upd, -0.01 * rb["dconv_w"][l], rtol=0, atol=1e-12 * max(1.0, np.abs(upd).max()))
