@@ -47,7 +47,9 @@ def test_argument_validation_happens_on_the_host():
     assert L.vgg_conv3x3_fwd(0, 0, 4, 4, 16, 16, a, a, None, a, 1, None, 0, None) == -2
     assert L.vgg_conv3x3_fwd(0, 1, 4, 4, 16, 16, a + 4, a, None, a, 1, None, 0, None) == -4
     assert L.vgg_conv3x3_fwd(0, 1, 4, 4, 3, 16, a, a, None, a, 1, None, 0, None) == -5   # needs a padded copy
-    assert L.vgg_conv3x3_bwd_weight(1, 1, 4, 4, 16, 16, a, a, a, None, a, 1 << 30, None) == -7  # bf16 training
+    assert L.vgg_conv3x3_bwd_weight(1, 1, 4, 4, 16, 20, a, a, a, None, a, 1 << 30, None) == -7  # bf16: Cout % 8
+    assert L.vgg_conv3x3_bwd_weight(0, 1, 4, 4, 16, 18, a, a, a, None, a, 1 << 30, None) == -7  # fp32: Cout % 4
+    assert L.vgg_conv3x3_bwd_weight(1, 1, 4, 4, 16, 16, a, a, a, None, None, 0, None) == -5
     assert L.vgg_conv3x3_bwd_weight(0, 1, 4, 4, 16, 16, a, a, a, None, None, 0, None) == -5
     assert L.vgg_maxpool2x2(0, 1, 5, 4, 8, a, a, None, None) == -2                        # odd H
     assert L.vgg_maxpool2x2(0, 1, 4, 4, 8, None, a, None, None) == -1
@@ -76,7 +78,13 @@ def test_model_level_validation_and_sizes():
     assert L.vgg19_forward(C.byref(cfg), a, a, a, a, None, 0, None) == -5
     assert L.vgg19_forward(C.byref(bad), a, a, a, a, a, 1 << 40, None) == -2
     assert L.vgg19_forward(None, a, a, a, a, a, 1 << 40, None) == -1
-    assert L.vgg19_train_step(C.byref(bf), a, a, a, 1 << 40, None, a, a, a, 1 << 40, None) == -7
+    assert L.vgg19_train_step(C.byref(bf), a, a, a, 1 << 40, None, a, a, a, 1 << 40, None) == -7      # no master copy
+    bfm = B.make_config(B.BF16, 2, 32, 32, 512, 10, 0.01, B.FLAG_FP32_MASTER)
+    assert B.vgg19_train_workspace_bytes(bfm) > 0
+    assert B.vgg19_packed_bytes(bfm) > B.vgg19_packed_bytes(bf) + B.vgg19_packed_bytes(cfg) - 9 * 64 * 32 * 4
+    assert L.vgg19_train_step(C.byref(bfm), a, a, a, B.vgg19_packed_bytes(bf), None, a, a, a, 1 << 40, None) == -5
+    assert B.vgg19_packed_bytes(B.make_config(B.F32, 2, 32, 32, 512, 10, 0.01, B.FLAG_FP32_MASTER)) == 0
+    assert B.vgg19_packed_bytes(B.make_config(B.BF16, 2, 32, 32, 512, 10, 0.01, 2)) == 0
     full = B.make_config(B.F32, 100, 224, 224, 4096, 1000)
     assert B.vgg19_packed_bytes(full) >= 143667240 * 4
 
