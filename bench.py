@@ -118,14 +118,15 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
     return res
 
 
-def run_train_bench(N, steps, inp_seed=0):
-    """fp32 training step (forward, cross-entropy, backward, SGD) at the same shapes: extra context."""
+def run_train_bench(N, steps, inp_seed=0, dtype_name="f32", extras=True):
+    """Training step (forward, cross-entropy, backward, SGD) at the same shapes: extra context.  bf16: bf16
+    operands, fp32 sums, fp32 master parameters."""
     import torch
     from paper_1810_09868_amd import binding as B
     from paper_1810_09868_amd import synth
     from paper_1810_09868_amd.model import Vgg19
     inp = synth.full_config(N, seed=inp_seed)
-    m = Vgg19(B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
+    m = Vgg19(B.BF16 if dtype_name == "bf16" else B.F32, N, 224, 224, 4096, 1000, lr=0.01, training=True)
     m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
     x = torch.from_numpy(inp.x).cuda()
     lab = torch.from_numpy(inp.labels).cuda()
@@ -157,11 +158,15 @@ def run_train_bench(N, steps, inp_seed=0):
     flops = 3 * conv - conv_flops(N, 0) + 3 * fc   # no data gradient for the first convolution
     del m
     torch.cuda.empty_cache()
-    return {"workload": "configs[4]: fp32 training step, batch %d, 3x224x224 (forward, mean cross-entropy, backward, SGD lr 0.01)" % N,
-            "dtype": "f32", "ms_per_step": dt * 1e3, "images_per_s": N / dt, "tflops": flops / dt / 1e12,
-            "pct_fp32_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS["f32"], "ms_by_kind": by_kind,
-            "as_one_graph": {"steps_per_graph": steps, "ms_per_step": dt_graph * 1e3},
-            "tiny_config_loop": tiny_loop_bench()}
+    res = {"workload": ("configs[4]: fp32 training step" if dtype_name == "f32" else
+                        "configs[4] with bf16 operands, fp32 sums and fp32 master parameters: training step") +
+                       ", batch %d, 3x224x224 (forward, mean cross-entropy, backward, SGD lr 0.01)" % N,
+           "dtype": dtype_name, "ms_per_step": dt * 1e3, "images_per_s": N / dt, "tflops": flops / dt / 1e12,
+           "pct_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS[dtype_name], "ms_by_kind": by_kind,
+           "as_one_graph": {"steps_per_graph": steps, "ms_per_step": dt_graph * 1e3}}
+    if extras:
+        res["tiny_config_loop"] = tiny_loop_bench()
+    return res
 
 
 def tiny_loop_bench(K=50):
@@ -317,6 +322,7 @@ def main():
                             "roofline": sec["roofline"]}
     if not a.no_secondary:
         out["train_step"] = run_train_bench(a.batch, max(2, a.steps // 5))
+        out["train_step_bf16"] = run_train_bench(a.batch, max(2, a.steps // 2), dtype_name="bf16", extras=False)
         out["batch_sweep"] = batch_sweep(a.dtype, (1, 10), max(5, a.steps))
     out["mfma_loop_ceiling"] = mfma_loop_ceiling()
     if not a.no_cpu_baseline:
