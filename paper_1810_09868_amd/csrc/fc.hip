@@ -230,19 +230,35 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[x][y][e] = 0.f;
 
-    for (int n0 = 0; n0 < N; n0 += 32) {
-        __syncthreads();
-        for (int idx = tid; idx < 32 * 32; idx += 256) {
+    // The 32 batch rows of a step are requested one step ahead; barriers without the fence of
+    // __syncthreads(), which would wait for those loads.
+    auto barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    uint4 vd[4], va[4];
+    auto request = [&](int n0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = tid + q * 256;
             const int seg = idx & 31, row = idx >> 5;
-            uint4 vd = make_uint4(0, 0, 0, 0), va = make_uint4(0, 0, 0, 0);
+            vd[q] = make_uint4(0, 0, 0, 0);
+            va[q] = make_uint4(0, 0, 0, 0);
             if (n0 + row < N) {
-                vd = load_row4(dz + (size_t)(n0 + row) * Out, o0 + seg * 4, Out, (Out & 3) == 0);
-                va = load_row4(a + (size_t)(n0 + row) * In, i0 + seg * 4, In, (In & 3) == 0);
+                vd[q] = load_row4(dz + (size_t)(n0 + row) * Out, o0 + seg * 4, Out, (Out & 3) == 0);
+                va[q] = load_row4(a + (size_t)(n0 + row) * In, i0 + seg * 4, In, (In & 3) == 0);
             }
-            *reinterpret_cast<uint4 *>(Ds + row * ROW + seg * 16) = vd;
-            *reinterpret_cast<uint4 *>(As + row * ROW + seg * 16) = va;
         }
-        __syncthreads();
+    };
+    request(0);
+    for (int n0 = 0; n0 < N; n0 += 32) {
+        barrier();  // the previous step's fragment reads are done
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = tid + q * 256;
+            const int seg = idx & 31, row = idx >> 5;
+            *reinterpret_cast<uint4 *>(Ds + row * ROW + seg * 16) = vd[q];
+            *reinterpret_cast<uint4 *>(As + row * ROW + seg * 16) = va[q];
+        }
+        barrier();  // the staged rows are visible
+        if (n0 + 32 < N) request(n0 + 32);
 #pragma unroll 4
         for (int s = 0; s < 16; ++s) {
             const int n = 2 * s + kp;
@@ -319,26 +335,48 @@ __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[x][j][e] = 0.f;
 
-    for (int oc = o_begin; oc < o_end; oc += 16) {
-        __syncthreads();
-        for (int idx = tid; idx < 128 * 4; idx += 256) {
-            const int seg = idx & 3, row = idx >> 2;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row0 + row < p.N)
-                v = load_row4(p.dz + (size_t)(row0 + row) * p.Out, oc + seg * 4, o_end, (p.Out & 3) == 0);
-            *reinterpret_cast<uint4 *>(Ds + row * kFcRow + seg * 16) = v;
-        }
-        __syncthreads();
+    // Operands of a chunk of 16 outputs are requested one chunk ahead: the weight stream from HBM never
+    // pauses for the staging and the MFMAs.  The barriers are issued without the fence that
+    // __syncthreads() carries (it would wait for the loads in flight); they only order LDS accesses.
+    auto barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    f32x4 w_next[2][4];
+    uint4 dz_next[2];
+    auto request = [&](int oc) __attribute__((always_inline)) {
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            // this lane's four contraction indices: oc + 8g + 4*khalf + e
-            f32x4 wv4[4];
+        for (int q = 0; q < 2; ++q) {
+            const int idx = tid + q * 256;
+            const int seg = idx & 3, row = idx >> 2;
+            dz_next[q] = make_uint4(0, 0, 0, 0);
+            if (row0 + row < p.N)
+                dz_next[q] = load_row4(p.dz + (size_t)(row0 + row) * p.Out, oc + seg * 4, o_end, (p.Out & 3) == 0);
+        }
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
+                // this lane's four contraction indices of half g: oc + 8g + 4*khalf + e
                 const int o = oc + g * 8 + khalf * 4 + e;
-                wv4[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (iok && o < o_end) wv4[e] = *reinterpret_cast<const f32x4 *>(p.w + (size_t)o * p.In + icol);
+                w_next[g][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (iok && o < o_end) w_next[g][e] = *reinterpret_cast<const f32x4 *>(p.w + (size_t)o * p.In + icol);
             }
+    };
+    if (o_begin < o_end) request(o_begin);
+    for (int oc = o_begin; oc < o_end; oc += 16) {
+        barrier();  // the previous chunk's fragment reads are done
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int idx = tid + q * 256;
+            *reinterpret_cast<uint4 *>(Ds + (idx >> 2) * kFcRow + (idx & 3) * 16) = dz_next[q];
+        }
+        f32x4 wv4[2][4];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) wv4[g][e] = w_next[g][e];
+        barrier();  // the staged rows are visible
+        if (oc + 16 < o_end) request(oc + 16);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const f32x4 af = *reinterpret_cast<const f32x4 *>(Ds + (wr * 64 + x * 32 + r) * kFcRow + g * 32 + khalf * 16);
@@ -346,7 +384,7 @@ __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        acc[x][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], wv4[e][j], acc[x][j], 0, 0, 0);
+                        acc[x][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], wv4[g][e][j], acc[x][j], 0, 0, 0);
             }
         }
     }
