@@ -139,15 +139,16 @@ int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const voi
                     const void *w_packed, const float *bias, void *y_nhwc, int relu, void *ws,
                     size_t ws_bytes, void *stream);
 
-/* vgg_conv3x3_fwd with the following 2x2 max-pool (vgg_maxpool2x2 without
- * argmax) fused into its epilogue: pooled is NHWC [N][H/2][W/2][Cout]; y may
- * be NULL, in which case the un-pooled tensor is never written.  Only for
+/* vgg_conv3x3_fwd with the following 2x2 max-pool (vgg_maxpool2x2) fused
+ * into its epilogue: pooled is NHWC [N][H/2][W/2][Cout]; argmax (may be NULL)
+ * gets one byte per pooled element as in vgg_maxpool2x2; y may be NULL, in
+ * which case the un-pooled tensor is never written.  Only for
  * H and W multiples of 16 and Cout a multiple of 16 bytes worth of elements
  * (VGG_ERR_UNSUPPORTED otherwise).  The contraction is never split here: the
  * workspace only has to hold the zero-padded copy of x, if one is needed. */
 int vgg_conv3x3_fwd_pool(int dtype, int N, int H, int W, int Cin, int Cout, const void *x_nhwc,
                          const void *w_packed, const float *bias, void *y_nhwc_or_null, void *pooled_nhwc,
-                         int relu, void *ws, size_t ws_bytes, void *stream);
+                         uint8_t *argmax_or_null, int relu, void *ws, size_t ws_bytes, void *stream);
 
 /* The network's first convolution (3 -> 64 channels), same definition as
  * vgg_conv3x3_fwd, but x is the canonical NCHW fp32 image batch [N][3][H][W]

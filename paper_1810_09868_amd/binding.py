@@ -75,7 +75,7 @@ def lib() -> C.CDLL:
             getattr(L, n).restype = _sz
             getattr(L, n).argtypes = [_i] * 6
         L.vgg_conv3x3_fwd.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
-        L.vgg_conv3x3_fwd_pool.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
+        L.vgg_conv3x3_fwd_pool.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
         L.vgg_conv3x3_fwd_first.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _i, _vp]
         L.vgg_conv3x3_bwd_data.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.vgg_conv3x3_bwd_weight.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -180,9 +180,9 @@ def vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, relu, ws=No
                                _ptr(ws), _nbytes(ws), _stream()), "vgg_conv3x3_fwd")
 
 
-def vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, pooled, relu, ws=None):
+def vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, pooled, relu, ws=None, argmax=None):
     _chk(lib().vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(y), _ptr(pooled),
-                                    int(relu), _ptr(ws), _nbytes(ws), _stream()), "vgg_conv3x3_fwd_pool")
+                                    _ptr(argmax), int(relu), _ptr(ws), _nbytes(ws), _stream()), "vgg_conv3x3_fwd_pool")
 
 
 def vgg_conv3x3_fwd_first(dtype, N, H, W, x_nchw, w_packed, bias, y, relu):

@@ -6,7 +6,7 @@
 namespace vgg {
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
-                  const void *mask, void *y, void *pool, int relu, void *part_ws, hipStream_t stream);
+                  const void *mask, void *y, void *pool, unsigned char *argmax, int relu, void *part_ws, hipStream_t stream);
 size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cout);
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
@@ -231,16 +231,19 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
     const char *cur = ws + L.x0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         char *out = ws + L.act[l];
-        // Inference on patch-tiled layers: the 2x2 maximum is taken in the convolution's epilogue and
-        // the un-pooled tensor is never written.
-        const bool fuse = !training && l > 0 && pool_after(l) && conv3x3_pool_fusable(dt, L.H[l], L.W[l], kConvCh[l][1]);
+        // On patch-tiled layers the 2x2 maximum (and, for training, its position) is taken in the
+        // convolution's epilogue and the un-pooled tensor is never written: the backward pass needs
+        // only the pooled tensor (next layer's input and ReLU mask) and the positions.
+        const bool fuse = l > 0 && pool_after(l) && conv3x3_pool_fusable(dt, L.H[l], L.W[l], kConvCh[l][1]);
         if (l == 0 && !training)
             VGG_STEP(rec, K_CONV, conv_first(dt, N, c->H, c->W, P.cinp[0], x, pk + P.conv_w[0],
                                             reinterpret_cast<const float *>(pk + P.conv_b[0]), out, 1, s));
         else
             VGG_STEP(rec, K_CONV, conv3x3_igemm(dt, N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1], cur, pk + P.conv_w[l],
                                                reinterpret_cast<const float *>(pk + P.conv_b[l]), nullptr,
-                                               fuse ? nullptr : out, fuse ? ws + L.pooled[l] : nullptr, 1, ws + L.convpart, s));
+                                               fuse ? nullptr : out, fuse ? ws + L.pooled[l] : nullptr,
+                                               fuse && training ? reinterpret_cast<uint8_t *>(ws + L.argmax[l]) : nullptr, 1,
+                                               ws + L.convpart, s));
         cur = out;
         if (fuse) {
             rec.skip(K_POOL);  // fused into the launch above; listed so that the plan still shows five pools
@@ -321,7 +324,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
             VGG_STEP(rec, K_OTHER, flip_packed_w(dt, P.cinp[l], Cout, Cout, F(pm + Pm.conv_w[l]), ws + L.wflip, s));
             VGG_STEP(rec, K_DGRAD, conv3x3_igemm(dt, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
-                                                gbuf[cur ^ 1], nullptr, 0, ws + L.convpart, s));
+                                                gbuf[cur ^ 1], nullptr, nullptr, 0, ws + L.convpart, s));
             cur ^= 1;
         }
     }
@@ -461,7 +464,7 @@ size_t vgg_conv3x3_fwd_workspace_bytes(int dtype, int N, int H, int W, int Cin, 
 }
 
 static int conv_fwd_common(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
-                           void *y, void *pooled, int relu, void *ws, size_t ws_bytes, void *stream)
+                           void *y, void *pooled, uint8_t *argmax, int relu, void *ws, size_t ws_bytes, void *stream)
 {
     if (!x || !w || (!y && !pooled)) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
@@ -483,21 +486,22 @@ static int conv_fwd_common(int dtype, int N, int H, int W, int Cin, int Cout, co
         part += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
     }
     if (!part_bytes) part = nullptr;
-    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, pooled, relu ? 1 : 0, part, s);
+    return conv3x3_igemm(dtype, N, H, W, cp, Cout, x, w, bias, nullptr, y, pooled, argmax, relu ? 1 : 0, part, s);
 }
 
 int vgg_conv3x3_fwd(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
                     void *y, int relu, void *ws, size_t ws_bytes, void *stream)
 {
     if (!y) return VGG_ERR_NULL;
-    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y, nullptr, relu, ws, ws_bytes, stream);
+    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y, nullptr, nullptr, relu, ws, ws_bytes, stream);
 }
 
 int vgg_conv3x3_fwd_pool(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *w, const float *bias,
-                         void *y_or_null, void *pooled, int relu, void *ws, size_t ws_bytes, void *stream)
+                         void *y_or_null, void *pooled, uint8_t *argmax_or_null, int relu, void *ws, size_t ws_bytes,
+                         void *stream)
 {
     if (!pooled) return VGG_ERR_NULL;
-    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y_or_null, pooled, relu, ws, ws_bytes, stream);
+    return conv_fwd_common(dtype, N, H, W, Cin, Cout, x, w, bias, y_or_null, pooled, argmax_or_null, relu, ws, ws_bytes, stream);
 }
 
 int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, const void *w, const float *bias, void *y,
@@ -538,7 +542,7 @@ int vgg_conv3x3_bwd_data(int dtype, int N, int H, int W, int Cin, int Cout, cons
         part += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
     }
     if (!conv3x3_igemm_workspace(dtype, N, H, W, cp, Cin)) part = nullptr;
-    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, nullptr, 0, part, s);
+    return conv3x3_igemm(dtype, N, H, W, cp, Cin, g, w_tf, nullptr, relu_src, dx, nullptr, nullptr, 0, part, s);
 }
 
 size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)

@@ -44,6 +44,7 @@ struct ConvArgs {
     int relu;
     int tiles_n;        // number of column tiles
     int rowsA;          // LDS rows reserved for the halo
+    unsigned char *argmax;  // with pool, optional: [N][H/2][W/2][Cout], 2*dh+dw of the first maximum of each window
     float *part;        // [ksplit][M][Cout] partial sums when the contraction is split over workgroups, else null
     int ksplit;         // workgroups per tile (>= 1)
     int kchunks;        // channel chunks per workgroup
@@ -190,6 +191,7 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
                     // windows; lane = (window, 16-byte segment).  Window (dx) = rows 2dx, 2dx+1, 16+2dx, 17+2dx.
                     const int win = lane >> 3;
                     T best[VEC];
+                    unsigned char which[VEC];   // k = 2*dh + dw of the first maximum (replaced only by a strictly greater value)
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const int row = (k >> 1) * kTileW + 2 * win + (k & 1);
@@ -198,7 +200,7 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
                         __builtin_memcpy(ve, &v, 16);
 #pragma unroll
                         for (int c = 0; c < VEC; ++c)
-                            if (k == 0 || Elem<T>::load(ve + c) > Elem<T>::load(best + c)) best[c] = ve[c];
+                            if (k == 0 || Elem<T>::load(ve + c) > Elem<T>::load(best + c)) { best[c] = ve[c]; which[c] = (unsigned char)k; }
                     }
                     const int j = wm * (BM / WM) + i * 32;  // first tile row of this block (even patch row)
                     const int ph = (org.h0 + j / kTileW) >> 1, pw = (org.w0 >> 1) + win;
@@ -206,7 +208,9 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
                         u32x4 v;
                         __builtin_memcpy(&v, best, 16);
                         T *po = reinterpret_cast<T *>(p.pool);
-                        *reinterpret_cast<u32x4 *>(po + (((size_t)org.n * (p.g.H >> 1) + ph) * (p.g.W >> 1) + pw) * p.Cout + colbase) = v;
+                        const size_t at = (((size_t)org.n * (p.g.H >> 1) + ph) * (p.g.W >> 1) + pw) * p.Cout + colbase;
+                        *reinterpret_cast<u32x4 *>(po + at) = v;
+                        if (p.argmax) __builtin_memcpy(p.argmax + at, which, VEC);
                     }
                 }
                 if (y == nullptr) continue;
@@ -721,10 +725,11 @@ bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout)
 }
 
 // x: [N*H*W][CinP], w: [9][Cout][CinP] (elements of dtype); y: [N*H*W][Cout].
-// pool (optional): 2x2 max of y, only when conv3x3_pool_fusable(); y may then be null.
+// pool (optional): 2x2 max of y, only when conv3x3_pool_fusable(); y may then be null; argmax (optional, with pool).
 // part_ws: conv3x3_igemm_workspace() bytes, or null (then the contraction is never split).
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w,
-                  const float *bias, const void *mask, void *y, void *pool, int relu, void *part_ws, hipStream_t stream)
+                  const float *bias, const void *mask, void *y, void *pool, unsigned char *argmax, int relu, void *part_ws,
+                  hipStream_t stream)
 {
     if (pool && !conv3x3_pool_fusable(dtype, H, W, Cout)) return VGG_ERR_UNSUPPORTED;
     ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, pool != nullptr);
@@ -736,6 +741,7 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     a.mask = static_cast<const char *>(mask);
     a.y = static_cast<char *>(y);
     a.pool = static_cast<char *>(pool);
+    a.argmax = pool ? argmax : nullptr;
     a.CinP = CinP; a.Cout = Cout;
     a.relu = relu; a.tiles_n = 0; a.rowsA = 0;
     a.part = c.ksplit > 1 ? static_cast<float *>(part_ws) : nullptr;

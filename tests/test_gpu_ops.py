@@ -95,11 +95,20 @@ def test_conv3x3_fwd_with_fused_pool(dtype, shape):
     # the pooled tensor is exactly the 2x2 maximum of what the same launch wrote un-pooled
     pgpu, _ = R.maxpool2x2(from_nhwc(y))
     assert np.array_equal(from_nhwc(pooled), pgpu)
-    # un-pooled output suppressed
+    # un-pooled output suppressed; positions of the maxima requested
     pooled2 = torch.empty_like(pooled)
-    B.vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), None, pooled2, 1)
+    arg = torch.full((N, H // 2, W // 2, Cout), 255, dtype=torch.uint8, device="cuda")
+    B.vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), None, pooled2, 1, argmax=arg)
     torch.cuda.synchronize()
     assert torch.equal(pooled, pooled2)
+    # bit-exact against the first-maximum rule applied to what the launch wrote un-pooled
+    _, agpu = R.maxpool2x2(from_nhwc(y))
+    assert np.array_equal(arg.permute(0, 3, 1, 2).cpu().numpy(), agpu)
+    # and the same bytes as the stand-alone pooling kernel gives
+    arg2 = torch.empty_like(arg)
+    B.vgg_maxpool2x2(dtype, N, H, W, Cout, y, pooled2, arg2)
+    torch.cuda.synchronize()
+    assert torch.equal(arg, arg2) and torch.equal(pooled, pooled2)
     with pytest.raises(B.VggError):
         B.vgg_conv3x3_fwd_pool(dtype, N, 14, 14, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), None, pooled2, 1)
 
