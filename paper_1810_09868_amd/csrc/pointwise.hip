@@ -343,22 +343,31 @@ int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int fli
 
 // Packed-forward fp32 [9][Cout][CinP] -> the flipped operand [9][Cin'][CoutP] where
 // Cin' = CinP rows are kept (padding rows are zero anyway).
+// One 32 x 32 (ci, co) block of one tap per workgroup, transposed through LDS so that both the reads
+// (ci contiguous) and the writes (co contiguous) are coalesced.
 template <typename TD>
-__global__ void flip_packed_w_kernel(const float *__restrict__ src, TD *__restrict__ dst, int CinP, int Cout, int CoutP)
+__global__ __launch_bounds__(256) void flip_packed_w_kernel(const float *__restrict__ src, TD *__restrict__ dst, int CinP, int Cout,
+                                                            int CoutP)
 {
-    const size_t total = (size_t)9 * CinP * CoutP;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int co = (int)(idx % CoutP);
-    const int ci = (int)((idx / CoutP) % CinP);
-    const int t = (int)(idx / ((size_t)CoutP * CinP));
-    Elem<TD>::store(dst + idx, co < Cout ? src[((size_t)(8 - t) * Cout + co) * CinP + ci] : 0.f);
+    __shared__ float tile[32][33];
+    const int t = blockIdx.z, ci0 = blockIdx.x * 32, co0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int co = co0 + r, ci = ci0 + tx;
+        tile[r][tx] = (co < Cout && ci < CinP) ? src[((size_t)(8 - t) * Cout + co) * CinP + ci] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int ci = ci0 + r, co = co0 + tx;
+        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + ((size_t)t * CinP + ci) * CoutP + co, tile[tx][r]);
+    }
 }
 
 int flip_packed_w(int dst_dtype, int CinP, int Cout, int CoutP, const float *src, void *dst, hipStream_t s)
 {
-    const size_t total = (size_t)9 * CinP * CoutP;
-    const dim3 grid((unsigned)((total + 255) / 256));
+    const dim3 grid((unsigned)((CinP + 31) / 32), (unsigned)((CoutP + 31) / 32), 9);
     if (dst_dtype == VGG_BF16)
         hipLaunchKernelGGL(flip_packed_w_kernel<bf16_t>, grid, dim3(256), 0, s, src, (bf16_t *)dst, CinP, Cout, CoutP);
     else
