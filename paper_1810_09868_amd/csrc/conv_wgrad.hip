@@ -50,9 +50,49 @@ struct WgradArgs {
 
 // Taps [T0, T0 + NT) of one wave: the main loop over the workgroup's tiles and the final sums.
 // S0: MFMA step before which the wave prepares the next tile's copies.
-template <int T0, int NT, int S0>
+// Patch tiles of the weight-gradient kernel: 4 rows x TW columns of one image (TW = 16 or 14, so that the
+// VGG widths 224, 112 and 56, 28 divide), halo 6 x (TW + 2).  Unlike the linear tiles (TW = 0, TileGeom
+// mode 0) their halo rows are an affine function of the tile row, so every x address of the main loop is
+// one per-lane base plus an immediate.  p.geo carries N, H, W, tiles_w, tiles_hw and their divisions.
+template <int TW>
+__device__ __forceinline__ TileOrigin wg_origin(const TileGeom &g, int tile)
+{
+    if (TW == 0) return tile_origin(g, tile);
+    TileOrigin o;
+    o.n = fast_div(tile, g.dTilesHW);
+    const int rem = tile - o.n * g.tiles_hw;
+    const int ty = fast_div(rem, g.dTilesW);
+    o.h0 = ty * 4;
+    o.w0 = (rem - ty * g.tiles_w) * TW;
+    o.m0 = 0; o.q0 = 0;
+    return o;
+}
+// output pixel of tile row j (-1: none) and, for linear tiles, its halo row
+template <int TW>
+__device__ __forceinline__ void wg_row(const TileGeom &g, const TileOrigin &o, int j, int &m, int &hrow)
+{
+    if (TW == 0) { tile_row(g, o, j, m, hrow); return; }
+    constexpr int D = TW ? TW : 1;
+    const int dy = j / D, dx = j - dy * D;
+    const int h = o.h0 + dy, w = o.w0 + dx;
+    m = (j < 4 * TW && h < g.H && w < g.W) ? (o.n * g.H + h) * g.W + w : -1;
+    hrow = 0;
+}
+template <int TW>
+__device__ __forceinline__ int wg_halo_pixel(const TileGeom &g, const TileOrigin &o, int i)
+{
+    if (TW == 0) return halo_pixel(g, o, i);
+    const int hy = i / (TW + 2), hx = i - hy * (TW + 2);
+    const int h = o.h0 - 1 + hy, w = o.w0 - 1 + hx;
+    if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
+    return (o.n * g.H + h) * g.W + w;
+}
+
+template <int T0, int NT, int S0, int TW>
 __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
 {
+    constexpr bool PATCH = TW != 0;
+    constexpr int PK = PATCH ? 4 * TW : kPK;           // pixels of a tile that are multiplied (g is staged as kPK rows)
     const int buf_bytes = kPK * kGRow + p.SX * kXRow;   // [kPK][256] g rows, then [SX][128] x rows
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -98,12 +138,12 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
     };
     constexpr int kXBatch = 3;                 // x blocks of a wave whose copies are spread over the steps
     constexpr int kOps = kGOps + kXBatch;      // copies that are spread over the MFMA steps
-    static_assert(S0 + kOps <= kPK / 4, "one copy per MFMA step");
+    static_assert(S0 + kOps <= PK / 4, "one copy per MFMA step");
     // lane l looks up halo row (l & 7) of this wave's x block k0 + (l >> 3) (blocks k0 .. k0 + 7)
     auto x_lookup = [&](const TileOrigin &org, int k0) __attribute__((always_inline)) {
         const int kk = k0 + (lane >> 3);
         const int i = (wv + kWaves * kk) * 8 + (lane & 7);
-        return (kk < nxw && i < p.geo.S) ? halo_pixel(p.geo, org, i) : -1;
+        return (kk < nxw && i < p.geo.S) ? wg_halo_pixel<TW>(p.geo, org, i) : -1;
     };
     // source addresses of g copy k / of x copy k of a lookup; m_l: output pixel of tile row `lane`
     auto g_src = [&](int m_l, int k) __attribute__((always_inline)) {
@@ -127,13 +167,13 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
         }
     };
 
-    const int wrow0 = __builtin_amdgcn_readfirstlane(wp * (kPK / 2));
+    const int wrow0 = __builtin_amdgcn_readfirstlane(wp * (PK / 2));
     const int nfirst = min(nxw, kXBatch);
     int hrow_l = 0;  // halo row (tap 0,0) of tile row `lane` of the tile being multiplied
     if (t_begin < t_end) {
-        const TileOrigin org0 = tile_origin(p.geo, t_begin);
+        const TileOrigin org0 = wg_origin<TW>(p.geo, t_begin);
         int m_l;
-        tile_row(p.geo, org0, lane, m_l, hrow_l);
+        wg_row<TW>(p.geo, org0, lane, m_l, hrow_l);
 #pragma unroll
         for (int k = 0; k < kGOps; ++k) dma(g_src(m_l, k), g_dst(smem, k));
         const int px_l = x_lookup(org0, 0);
@@ -157,9 +197,9 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
         const int ncopy = more ? kGOps + nfirst : 0;
         auto prepare = [&]() __attribute__((always_inline)) {
             // all cross-lane reads first, then one wait: each of them has LDS latency
-            orgn = tile_origin(p.geo, more ? tile + 1 : tile);
+            orgn = wg_origin<TW>(p.geo, more ? tile + 1 : tile);
             int m_l;
-            tile_row(p.geo, orgn, lane, m_l, hrow_next);
+            wg_row<TW>(p.geo, orgn, lane, m_l, hrow_next);
             const int px_l = x_lookup(orgn, 0);
 #pragma unroll
             for (int k = 0; k < kGOps; ++k) srcs[k] = g_src(m_l, k);
@@ -173,10 +213,21 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
         const char *ga = Gs + (wrow0 + kp) * kGRow + (((wc * 32 + r) ^ (kp << 5)) << 2);
         // operands of step s+1 are read from LDS before the MFMAs of step s are issued
         float a_next, b_next[NT];
+        // (PATCH) tile row j = wrow0 + 2s + kp sits in halo row (j / TW) * (TW + 2) + j % TW; TW is even and
+        // wrow0 two whole patch rows, so the pixel pair of a step never straddles a patch row
+        const char *xpatch = Xs + (wp * 2 * (TW + 2) + kp) * kXRow + r * 4;
         auto fetch = [&](int s) __attribute__((always_inline)) {
+            a_next = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
+            if (PATCH) {
+                constexpr int D = PATCH ? TW : 2;
+                const int ro = (((2 * s) / D) * (TW + 2) + (2 * s) % D) * kXRow;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    b_next[t] = *reinterpret_cast<const float *>(xpatch + ro + (((T0 + t) / 3) * (TW + 2) + (T0 + t) % 3) * kXRow);
+                return;
+            }
             const int h0 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s);
             const int h1 = __builtin_amdgcn_readlane(hrow_l, wrow0 + 2 * s + 1);
-            a_next = *reinterpret_cast<const float *>(ga + s * 2 * kGRow);
             const char *xb = Xs + (kp ? h1 : h0) * kXRow + r * 4;
 #pragma unroll
             for (int t = 0; t < NT; ++t)
@@ -184,7 +235,7 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
         };
         fetch(0);
 #pragma unroll
-        for (int s = 0; s < kPK / 4; ++s) {
+        for (int s = 0; s < PK / 4; ++s) {
             if (s == S0) prepare();
             if (s >= S0 && s - S0 < kOps && s - S0 < ncopy)
                 dma(srcs[s - S0], s - S0 < kGOps ? g_dst(nbase, s - S0) : x_dst(nbase, s - S0 - kGOps));
@@ -192,7 +243,7 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
             float bv[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) bv[t] = b_next[t];
-            if (s + 1 < kPK / 4) fetch(s + 1);
+            if (s + 1 < PK / 4) fetch(s + 1);
             gsum += a;
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[t], acc[t], 0, 0, 0);
@@ -239,12 +290,13 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs &p, char *smem)
 // accumulator registers of a wave, so four waves fit on a SIMD; a wave of each tap group lands on
 // every SIMD (wave w runs on SIMD w % 4), which balances the 5:4 split; the two groups also prepare
 // the next tile at different points of a tile, so a SIMD always has waves that are multiplying.
+template <int TW>
 __global__ __launch_bounds__(kWaves * 64, 4) void conv3x3_wgrad_kernel(WgradArgs p)
 {
     extern __shared__ __align__(16) char smem[];
     // (wave-uniform branch: both bodies execute the same sequence of barriers)
-    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 8) == 0) wgrad_body<0, 5, 0>(p, smem);
-    else wgrad_body<5, 4, kPK / 8>(p, smem);
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 8) == 0) wgrad_body<0, 5, 0, TW>(p, smem);
+    else wgrad_body<5, 4, (TW ? 4 * TW : kPK) / 8, TW>(p, smem);
 }
 
 // Layers with at most three input channels (the first one): (tap, ci) pairs are the <= 27 columns
@@ -428,9 +480,25 @@ void wgrad_launch_reduce(const float *part, float *out, size_t n, int splits, hi
     launch_reduce(part, out, n, splits, stream);
 }
 
+// Patch width of the general kernel for an image size: 16 or 14 where the image width divides into
+// patches (the last patch row of an image may stick out at the bottom: at most three rows of zeros),
+// else 0 (linear tiles).
+static int wgrad_patch_width(int H, int W) { return H < 4 ? 0 : (W % 16 == 0 ? 16 : (W % 14 == 0 ? 14 : 0)); }
+
 static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a, bool thin = false)
 {
     a.geo = make_tile_geom(N, H, W, kPK);
+    const int TW = thin ? 0 : wgrad_patch_width(H, W);
+    if (TW != 0) {
+        a.geo.mode = 1; a.geo.TH = 4; a.geo.TW = TW;
+        a.geo.tiles_w = W / TW;
+        a.geo.tiles_hw = a.geo.tiles_w * ((H + 3) / 4);
+        a.geo.dTilesW = make_fast_div(a.geo.tiles_w);
+        a.geo.dTilesHW = make_fast_div(a.geo.tiles_hw);
+        a.geo.ntiles = N * a.geo.tiles_hw;
+        a.geo.pitch = TW + 2;
+        a.geo.S = 6 * (TW + 2);
+    }
     a.SX = (a.geo.S + 7) & ~7;
     if (a.SX < 8 * kWaves) a.SX = 8 * kWaves;  // every wave copies at least one halo block
     a.CinP = CinP; a.Cout = Cout;
@@ -471,7 +539,11 @@ int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float 
     if (lds > 160 * 1024) return VGG_ERR_UNSUPPORTED;
     static bool configured = false;
     if (lds > 64 * 1024 && !configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<14>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_thin_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -481,8 +553,12 @@ int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float 
     const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
     if (thin)
         hipLaunchKernelGGL(conv3x3_wgrad_thin_kernel, grid, dim3(kWaves * 64), lds, stream, a, Cin);
+    else if (a.geo.mode == 1 && a.geo.TW == 16)
+        hipLaunchKernelGGL(conv3x3_wgrad_kernel<16>, grid, dim3(kWaves * 64), lds, stream, a);
+    else if (a.geo.mode == 1)
+        hipLaunchKernelGGL(conv3x3_wgrad_kernel<14>, grid, dim3(kWaves * 64), lds, stream, a);
     else
-        hipLaunchKernelGGL(conv3x3_wgrad_kernel, grid, dim3(kWaves * 64), lds, stream, a);
+        hipLaunchKernelGGL(conv3x3_wgrad_kernel<0>, grid, dim3(kWaves * 64), lds, stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
     launch_reduce(a.part, dw, nw, a.splits, stream);
     if (db) launch_reduce(a.dbpart, db, (size_t)Cout, a.splits, stream);
