@@ -220,7 +220,17 @@ def batch_sweep(dtype_name, batches, steps):
             m.forward(x)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
-        res.append({"batch": N, "ms_per_step": round(dt * 1e3, 4), "images_per_s": round(N / dt, 1)})
+        # the same passes recorded once and replayed as a single HIP graph
+        g = m.capture_forward(x, steps)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        dtg = (time.perf_counter() - t0) / steps
+        del g
+        res.append({"batch": N, "ms_per_step": round(dt * 1e3, 4), "images_per_s": round(N / dt, 1),
+                    "as_one_graph_ms_per_step": round(dtg * 1e3, 4)})
         del m
         torch.cuda.empty_cache()
     return res

@@ -263,7 +263,10 @@ int vgg19_forward(const vgg_config *cfg, const float *x_nchw, const void *packed
  * backward runs in fp32 from the master weights; the update goes to the fp32
  * master copy and the bf16 copy is refreshed from it.  labels int32 [N].  grads_or_null, when given, receives the
  * 38 gradient tensors in canonical layout.  loss (1 float) and logits
- * ([N][classes]) may be NULL. */
+ * ([N][classes]) may be NULL.  The fp32 update streams over the whole packed
+ * block: the alignment gaps between its tensors (never read by any kernel)
+ * take whatever the workspace holds at the matching positions, so zero the
+ * workspace once if the block is to be compared byte for byte. */
 int vgg19_train_step(const vgg_config *cfg, const float *x_nchw, const int32_t *labels,
                      void *packed_inout, size_t packed_bytes, const vgg19_params *grads_or_null,
                      float *loss, float *logits, void *ws, size_t ws_bytes, void *stream);

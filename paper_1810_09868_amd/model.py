@@ -32,7 +32,9 @@ class Vgg19:
         wsb = B.vgg19_train_workspace_bytes(self.cfg) if training else B.vgg19_forward_workspace_bytes(self.cfg)
         if wsb == 0:
             raise ValueError("configuration not supported for this mode")
-        self.ws = torch.empty((wsb,), dtype=torch.uint8, device="cuda")
+        # zeroed once: the update streams over the whole parameter block, alignment gaps included, and the
+        # gaps of the gradient block inside the workspace are never written by a kernel
+        self.ws = torch.zeros((wsb,), dtype=torch.uint8, device="cuda")
         self.logits = torch.empty((N, classes), dtype=torch.float32, device="cuda")
         self.probs = torch.empty((N, classes), dtype=torch.float32, device="cuda")
         self.loss = torch.zeros((1,), dtype=torch.float32, device="cuda")
@@ -69,6 +71,16 @@ class Vgg19:
         g = self._canon_buffers() if want_grads else None
         B.vgg19_train_step(self.cfg, x, labels, self.packed, B.make_params(**g) if g else None, self.loss,
                            self.logits, self.ws)
+        return g
+
+    def capture_forward(self, x: torch.Tensor, passes: int = 1, want_probs: bool = True) -> "torch.cuda.CUDAGraph":
+        """Records `passes` forward passes on the given batch into one HIP graph (call forward once before
+        capturing).  At small batches a pass is a few dozen short launches, and replaying them as one graph
+        removes the host's share of the latency."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(passes):
+                B.vgg19_forward(self.cfg, x, self.packed, self.logits, self.probs if want_probs else None, self.ws)
         return g
 
     def capture_train_steps(self, x: torch.Tensor, labels: torch.Tensor, steps: int) -> "torch.cuda.CUDAGraph":

@@ -296,6 +296,26 @@ def test_full_vgg19_forward_small_batches(dtype, N):
         _check_probs(probs[n:n + 1], logits[n:n + 1], ref, dtype)
 
 
+def test_forward_as_one_graph_matches_eager():
+    # replays of a recorded forward pass give bit-identical logits, also with eager work between replays
+    inp = synth.full_config(1, seed=3, with_labels=False)
+    m = Vgg19(B.BF16, 1, 224, 224, 4096, 1000)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    x = dev(inp.x)
+    m.forward(x)
+    torch.cuda.synchronize()
+    want_logits, want_probs = m.logits.clone(), m.probs.clone()
+    g = m.capture_forward(x, 2)
+    for _ in range(3):
+        m.logits.zero_(); m.probs.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(m.logits, want_logits) and torch.equal(m.probs, want_probs)
+        m.forward(dev(inp.x * 0.5))      # eager work on the same buffers in between
+        torch.cuda.synchronize()
+
+
 def test_full_vgg19_train_step_224_vs_oracle_batch2():
     inp = synth.vgg19_inputs(2, 224, 224, 4096, 1000, seed=1)
     ref = R.vgg19_train_step(inp.x, inp.labels, _f64(inp.conv_w), _f64(inp.conv_b), _f64(inp.fc_w),
