@@ -217,6 +217,118 @@ def _bf16_backward_kernels_on_oracle_tensors(inp):
     return worst
 
 
+_CONV = [(3, 64), (64, 64), (64, 128), (128, 128), (128, 256), (256, 256), (256, 256), (256, 256),
+         (256, 512), (512, 512), (512, 512), (512, 512), (512, 512), (512, 512), (512, 512), (512, 512)]
+_POOLED = (1, 3, 7, 11, 15)
+
+
+def _bf16_step_from_single_op_calls(inp, N, H, W, hidden, classes):
+    """The 38 gradients of one bf16 training step, computed by chaining the single-operation entry points
+    (each held to the oracle in test_gpu_ops.py and in the per-layer test above) from Python in the order
+    the model-level call documents.  Same kernels, same shapes, deterministic sums: vgg19_train_step must
+    reproduce these bit for bit, which pins its buffer plumbing without any tolerance."""
+    bf = torch.bfloat16
+    ws = lambda n: ws_bytes(n)
+    x = torch.empty((N, H, W, 32), dtype=bf, device="cuda")
+    B.vgg_nchw_to_nhwc(B.BF16, N, 3, H, W, 32, dev(inp.x), x)
+    acts_in, args, sizes = [], {}, []
+    h, w = H, W
+    cur = x
+    for l, (ci, co) in enumerate(_CONV):
+        acts_in.append(cur)
+        sizes.append((h, w))
+        cp = B.vgg_padded_channels(B.BF16, ci)
+        wp = torch.empty((9, co, cp), dtype=bf, device="cuda")
+        B.vgg_conv_pack_weights(B.BF16, ci, co, dev(inp.conv_w[l]), wp, 0)
+        wsb = ws(B.vgg_conv3x3_fwd_workspace_bytes(B.BF16, N, h, w, cp, co))
+        if l in _POOLED:
+            pooled = torch.empty((N, h // 2, w // 2, co), dtype=bf, device="cuda")
+            arg = torch.empty((N, h // 2, w // 2, co), dtype=torch.uint8, device="cuda")
+            if l > 0 and h % 16 == 0 and w % 16 == 0:      # pool taken in the convolution's epilogue
+                B.vgg_conv3x3_fwd_pool(B.BF16, N, h, w, cp, co, cur, wp, dev(inp.conv_b[l]), None, pooled, 1, wsb, argmax=arg)
+            else:
+                y = torch.empty((N, h, w, co), dtype=bf, device="cuda")
+                B.vgg_conv3x3_fwd(B.BF16, N, h, w, cp, co, cur, wp, dev(inp.conv_b[l]), y, 1, wsb)
+                B.vgg_maxpool2x2(B.BF16, N, h, w, co, y, pooled, arg)
+            args[l] = arg
+            cur = pooled
+            h, w = h // 2, w // 2
+        else:
+            y = torch.empty((N, h, w, co), dtype=bf, device="cuda")
+            B.vgg_conv3x3_fwd(B.BF16, N, h, w, cp, co, cur, wp, dev(inp.conv_b[l]), y, 1, wsb)
+            cur = y
+    flat = 512 * h * w
+    dims = [(flat, hidden), (hidden, hidden), (hidden, classes)]
+    # dense weights: the first layer's columns in H,W,C order (the order the NHWC tensor is flattened in)
+    fcw32 = [dev(inp.fc_w[0]).view(hidden, 512, h * w).permute(0, 2, 1).reshape(hidden, flat).contiguous(),
+             dev(inp.fc_w[1]), dev(inp.fc_w[2])]
+    a_in = [cur.reshape(N, flat)]
+    for l, (i, o) in enumerate(dims):
+        last = l == 2
+        z = torch.empty((N, o), dtype=torch.float32 if last else bf, device="cuda")
+        B.vgg_fc(B.BF16, N, i, o, a_in[l], fcw32[l].to(bf), dev(inp.fc_b[l]), z, B.F32 if last else B.BF16, 0 if last else 1,
+                 ws(B.vgg_fc_workspace_bytes(B.BF16, N, i, o)))
+        a_in.append(z)
+    logits = a_in[3]
+    probs = torch.empty_like(logits)
+    B.vgg_softmax(N, classes, logits, probs)
+    dz = torch.empty_like(logits)
+    loss = torch.zeros((1,), device="cuda")
+    B.vgg_softmax_xent_bwd(N, classes, probs, dev(inp.labels), loss, dz, ws(4 * N + 256))
+    g = dict(conv_w=[None] * 16, conv_b=[None] * 16, fc_w=[None] * 3, fc_b=[None] * 3)
+    for l in (2, 1, 0):
+        i, o = dims[l]
+        dw = torch.empty((o, i), device="cuda")
+        db = torch.empty((o,), device="cuda")
+        da = torch.empty((N, i), device="cuda")
+        B.vgg_fc_bwd(B.F32, N, i, o, a_in[l].float(), fcw32[l], dz, dw, db, da, 1, ws(B.vgg_fc_bwd_workspace_bytes(B.F32, N, i, o)))
+        g["fc_w"][l], g["fc_b"][l] = dw, db
+        dz = da
+    g["fc_w"][0] = g["fc_w"][0].view(hidden, h * w, 512).permute(0, 2, 1).reshape(hidden, flat).contiguous()
+    d = dz.to(bf).view(N, h, w, 512)
+    for l in range(15, -1, -1):
+        ci, co = _CONV[l]
+        hh, ww = sizes[l]
+        cp = B.vgg_padded_channels(B.BF16, ci)
+        if l in _POOLED:
+            up = torch.empty((N, hh, ww, co), dtype=bf, device="cuda")
+            B.vgg_maxpool2x2_bwd(B.BF16, N, hh, ww, co, d, args[l], up)
+            d = up
+        dwp = torch.empty((9, co, cp), device="cuda")
+        db = torch.empty((co,), device="cuda")
+        B.vgg_conv3x3_bwd_weight(B.BF16, N, hh, ww, cp, co, acts_in[l], d, dwp, db,
+                                 ws(B.vgg_conv3x3_bwd_weight_workspace_bytes(B.BF16, N, hh, ww, cp, co)))
+        g["conv_w"][l] = dwp[:, :, :ci].reshape(3, 3, co, ci).permute(2, 3, 0, 1).contiguous()
+        g["conv_b"][l] = db
+        if l > 0:
+            wtf = torch.empty((9, ci, co), dtype=bf, device="cuda")
+            B.vgg_conv_pack_weights(B.BF16, ci, co, dev(inp.conv_w[l]), wtf, 1)
+            dx = torch.empty((N, hh, ww, ci), dtype=bf, device="cuda")
+            B.vgg_conv3x3_bwd_data(B.BF16, N, hh, ww, ci, co, d, wtf, acts_in[l], dx,
+                                   ws(B.vgg_conv3x3_bwd_data_workspace_bytes(B.BF16, N, hh, ww, ci, co)))
+            d = dx
+    torch.cuda.synchronize()
+    return logits, loss, g
+
+
+@pytest.mark.parametrize("size", ["tiny", "224"])
+def test_bf16_train_step_equals_chained_single_op_calls(size):
+    if size == "tiny":
+        inp, shp = synth.tiny_config(seed=0), (2, 32, 32, 512, 10)
+    else:
+        inp, shp = synth.vgg19_inputs(2, 224, 224, 4096, 1000, seed=1), (2, 224, 224, 4096, 1000)
+    logits, loss, want = _bf16_step_from_single_op_calls(inp, *shp)
+    m = Vgg19(B.BF16, *shp, lr=0.01, training=True)
+    m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    got = m.train_step(dev(inp.x), dev(inp.labels), want_grads=True)
+    torch.cuda.synchronize()
+    assert torch.equal(m.logits, logits)
+    assert torch.equal(m.loss, loss)
+    for k in ("conv_w", "conv_b", "fc_w", "fc_b"):
+        for l, (a, b) in enumerate(zip(got[k], want[k])):
+            assert torch.equal(a, b), (k, l, float((a - b).abs().max()))
+
+
 def test_tiny_vgg19_train_step_bf16():
     _bf16_train_step_vs_oracle(synth.tiny_config(seed=0), 2, 32, 32, 512, 10)
 
