@@ -240,7 +240,7 @@ size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 }
 
 // x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
-// Cout must be a multiple of 8 and CinP of 32 (16-byte channel segments).
+// Cout and CinP must be multiples of 8 (16-byte channel segments).
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
                        void *ws, hipStream_t stream)
 {
