@@ -225,8 +225,8 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
                  float *probs, bool want_probs, char *ws, bool training, hipStream_t s, Recorder &rec)
 {
     const int dt = c->dtype, N = c->N;
-    // Training keeps a channel-padded NHWC copy of the images (the first layer's weight gradient
-    // reads it); inference feeds the NCHW batch straight to the first convolution.
+    // The first convolution reads the NCHW batch itself; training also keeps a channel-padded NHWC copy
+    // of the images, which the first layer's weight gradient reads.
     if (training) VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, P.cinp[0], x, ws + L.x0, s));
     const char *cur = ws + L.x0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
@@ -235,7 +235,7 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
         // convolution's epilogue and the un-pooled tensor is never written: the backward pass needs
         // only the pooled tensor (next layer's input and ReLU mask) and the positions.
         const bool fuse = l > 0 && pool_after(l) && conv3x3_pool_fusable(dt, L.H[l], L.W[l], kConvCh[l][1]);
-        if (l == 0 && !training)
+        if (l == 0)   // (reads the NCHW batch itself; the padded NHWC copy above is only the weight gradient's operand)
             VGG_STEP(rec, K_CONV, conv_first(dt, N, c->H, c->W, P.cinp[0], x, pk + P.conv_w[0],
                                             reinterpret_cast<const float *>(pk + P.conv_b[0]), out, 1, s));
         else

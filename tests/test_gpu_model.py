@@ -255,7 +255,10 @@ def _bf16_step_from_single_op_calls(inp, N, H, W, hidden, classes):
             h, w = h // 2, w // 2
         else:
             y = torch.empty((N, h, w, co), dtype=bf, device="cuda")
-            B.vgg_conv3x3_fwd(B.BF16, N, h, w, cp, co, cur, wp, dev(inp.conv_b[l]), y, 1, wsb)
+            if l == 0:      # the first convolution reads the NCHW batch itself
+                B.vgg_conv3x3_fwd_first(B.BF16, N, h, w, dev(inp.x), wp, dev(inp.conv_b[l]), y, 1)
+            else:
+                B.vgg_conv3x3_fwd(B.BF16, N, h, w, cp, co, cur, wp, dev(inp.conv_b[l]), y, 1, wsb)
             cur = y
     flat = 512 * h * w
     dims = [(flat, hidden), (hidden, hidden), (hidden, classes)]
