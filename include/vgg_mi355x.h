@@ -208,9 +208,11 @@ size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias,
            void *z, int z_dtype, int relu, void *ws, size_t ws_bytes, void *stream);
 
-/* fp32 only.  dw[o,i] = sum_n dz[n,o] a[n,i]; db[o] = sum_n dz[n,o] (db may
- * be NULL); if da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by
- * (a[n,i] > 0) when relu_mask != 0 (ReLU backward of the producer of a). */
+/* dw[o,i] = sum_n dz[n,o] a[n,i]; db[o] = sum_n dz[n,o] (db may be NULL); if
+ * da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by (a[n,i] > 0)
+ * when relu_mask != 0 (ReLU backward of the producer of a).  a and w are in
+ * `dtype`; dz, dw, db and da are always fp32.  VGG_BF16: dz is rounded to
+ * bf16 where it enters a product (not for db), sums are fp32. */
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz,
                float *dw, float *db, void *da, int relu_mask, void *ws, size_t ws_bytes,
@@ -259,9 +261,10 @@ int vgg19_forward(const vgg_config *cfg, const float *x_nchw, const void *packed
  * theta <- theta - cfg->lr * grad on the packed block in place.  VGG_F32,
  * or VGG_BF16 with VGG_FLAG_FP32_MASTER: activations, their gradients and
  * the weights the convolutions read are bf16, all sums fp32 (the matrix
- * unit's bf16 x bf16 -> fp32 of the paper's accelerator); the dense layers'
- * backward runs in fp32 from the master weights; the update goes to the fp32
- * master copy and the bf16 copy is refreshed from it.  labels int32 [N].  grads_or_null, when given, receives the
+ * unit's bf16 x bf16 -> fp32 of the paper's accelerator); gradients with
+ * respect to the dense layers' pre-activations are kept in fp32 and rounded
+ * where they enter a product; the update goes to the fp32 master copy and
+ * the bf16 copy is refreshed from it.  labels int32 [N].  grads_or_null, when given, receives the
  * 38 gradient tensors in canonical layout.  loss (1 float) and logits
  * ([N][classes]) may be NULL.  The fp32 update streams over the whole packed
  * block: the alignment gaps between its tensors (never read by any kernel)

@@ -266,8 +266,10 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     ``operand_round`` as in vgg19_forward (f must come from a forward pass with
     the same setting): the gradient that enters the convolution stack and the
     result of every data-gradient convolution are rounded, as are the
-    convolution weights the data gradient multiplies with; the dense layers'
-    backward products use the unrounded (master) weights and are not rounded.
+    weights a data gradient multiplies with (convolution and dense) and the
+    gradient with respect to a dense layer's pre-activation where it enters
+    one of that layer's two backward products; sums (bias gradients
+    included) are not rounded.
     """
     rd = operand_round if operand_round is not None else (lambda a: a)
     def relu_mask(pre, d):
@@ -278,11 +280,17 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     loss, dlogits = softmax_xent(f["probs"], labels)
     dfc_w = [None] * 3
     dfc_b = [None] * 3
-    dfc_w[2], dfc_b[2], dz2 = fc_bwd(f["z2"], fc_w[2], dlogits)
+    def dense_bwd(a, w, dz):
+        # with operand rounding the two products see the rounded dz and the rounded weights; the bias
+        # gradient is a plain sum of the unrounded dz
+        dw, _, da = fc_bwd(a, rd(w), rd(dz))
+        return dw, _f64(dz).sum(axis=0), da
+
+    dfc_w[2], dfc_b[2], dz2 = dense_bwd(f["z2"], fc_w[2], dlogits)
     dz2 = relu_mask(f["fc_pre"][1], dz2)
-    dfc_w[1], dfc_b[1], dz1 = fc_bwd(f["z1"], fc_w[1], dz2)
+    dfc_w[1], dfc_b[1], dz1 = dense_bwd(f["z1"], fc_w[1], dz2)
     dz1 = relu_mask(f["fc_pre"][0], dz1)
-    dfc_w[0], dfc_b[0], dflat = fc_bwd(f["flat"], fc_w[0], dz1)
+    dfc_w[0], dfc_b[0], dflat = dense_bwd(f["flat"], fc_w[0], dz1)
     d = rd(dflat.reshape(f["pool5"].shape))
     dconv_w = [None] * 16
     dconv_b = [None] * 16

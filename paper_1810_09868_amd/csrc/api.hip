@@ -40,6 +40,9 @@ int fc_forward(int dtype, int N, int In, int Out, const void *a, const void *w, 
 size_t fc_bwd_workspace(int N, int In, int Out);
 int fc_backward(int N, int In, int Out, const float *a, const float *w, const float *dz, float *dw, float *db, float *da,
                 int relu_mask, void *ws, hipStream_t s);
+size_t fc_bwd_bf16_workspace(int N, int In, int Out);
+int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, const float *dz, float *dw, float *db, float *da,
+                     int relu_mask, void *ws, hipStream_t s);
 
 namespace {
 
@@ -108,7 +111,7 @@ struct WsLayout {
     size_t convpart;                   // partial sums of convolutions whose contraction is split
     // training only
     size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
-    size_t a32, dflat32;               // bf16 training: fp32 copies of a dense layer's input / of the flatten gradient
+    size_t a32, dflat32;               // bf16 training: fp32 gradient with respect to the flattened pool output (a32 unused)
     size_t total;
     int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
 };
@@ -181,10 +184,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         L.wflip = b.take((size_t)9 * 512 * 512 * es);
         const bool mixed = c->dtype == VGG_BF16;
         L.grads = b.take(mixed ? packed_layout(c, true).total : P.total);
-        if (mixed) {
-            L.a32 = b.take(N * P.fc_in[0] * 4);
-            L.dflat32 = b.take(N * P.fc_in[0] * 4);
-        }
+        if (mixed) L.dflat32 = b.take(N * P.fc_in[0] * 4);
         size_t wg = 0, fb = 0;
         for (int l = 0; l < VGG19_NUM_CONV; ++l) {
             const size_t s = mixed ? conv3x3_wgrad_bf16_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1])
@@ -192,7 +192,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
             if (s > wg) wg = s;
         }
         for (int l = 0; l < VGG19_NUM_FC; ++l) {
-            const size_t s = fc_bwd_workspace(c->N, P.fc_in[l], P.fc_out[l]);
+            const size_t s = mixed ? fc_bwd_bf16_workspace(c->N, P.fc_in[l], P.fc_out[l]) : fc_bwd_workspace(c->N, P.fc_in[l], P.fc_out[l]);
             if (s > fb) fb = s;
         }
         L.wgws = b.take(wg);
@@ -273,8 +273,9 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
 {
     const int N = c->N, dt = c->dtype;
     // bf16: operands (activations, gradients with respect to activations, working weights) are bf16,
-    // sums fp32; the fp32 master parameters behind the bf16 block take the update.  The three dense
-    // layers' backward runs on the fp32 kernels, from the master weights and fp32 copies of its inputs.
+    // sums fp32; the fp32 master parameters behind the bf16 block take the update.  The gradients with
+    // respect to the dense layers' pre-activations stay fp32 between the dense layers and are rounded
+    // to bf16 as they enter a product.
     const bool mixed = dt == VGG_BF16;
     const PackedLayout Pm = mixed ? packed_layout(c, true) : P;
     char *pm = mixed ? pk + P.total : pk;
@@ -290,14 +291,14 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
     float *dflat = F(mixed ? ws + L.dflat32 : ws + L.gA);
     for (int l = 2; l >= 0; --l) {
         float *da = l == 0 ? dflat : fc_dz[l - 1];
-        const float *a = reinterpret_cast<const float *>(fc_in[l]);
-        if (mixed) {
-            VGG_STEP(rec, K_OTHER, convert(VGG_BF16, VGG_F32, (size_t)N * P.fc_in[l], fc_in[l], ws + L.a32, s));
-            a = F(ws + L.a32);
-        }
         if (!rec.skip(K_FCDW)) {
-            rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], a, F(pm + Pm.fc_w[l]), fc_dz[l], F(gr + Pm.fc_w[l]),
-                                 F(gr + Pm.fc_b[l]), da, 1, ws + L.fcbws, s);
+            if (mixed)
+                rec.rc = fc_backward_bf16(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const bf16_t *>(fc_in[l]),
+                                          reinterpret_cast<const bf16_t *>(pk + P.fc_w[l]), fc_dz[l], F(gr + Pm.fc_w[l]),
+                                          F(gr + Pm.fc_b[l]), da, 1, ws + L.fcbws, s);
+            else
+                rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const float *>(fc_in[l]), F(pk + P.fc_w[l]),
+                                     fc_dz[l], F(gr + P.fc_w[l]), F(gr + P.fc_b[l]), da, 1, ws + L.fcbws, s);
         }
         rec.skip(K_FCDA);  // issued by the same call; listed for the plan
     }
@@ -614,8 +615,8 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
 
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out)
 {
-    if (dtype != VGG_F32 || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
-    return fc_bwd_workspace(N, In, Out);
+    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
+    return dtype == VGG_F32 ? fc_bwd_workspace(N, In, Out) : fc_bwd_bf16_workspace(N, In, Out);
 }
 
 int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz, float *dw, float *db, void *da,
@@ -623,11 +624,14 @@ int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, 
 {
     if (!a || !w || !dz || !dw) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
-    if (dtype != VGG_F32) return VGG_ERR_UNSUPPORTED;
     if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(w) || !aligned16(dz) || !aligned16(dw) || (da && !aligned16(da)) || (ws && !aligned16(ws)))
         return VGG_ERR_ALIGN;
-    if (da && (!ws || ws_bytes < fc_bwd_workspace(N, In, Out))) return VGG_ERR_WORKSPACE;
+    if (da && (!ws || ws_bytes < vgg_fc_bwd_workspace_bytes(dtype, N, In, Out))) return VGG_ERR_WORKSPACE;
+    if (dtype == VGG_BF16)
+        return fc_backward_bf16(N, In, Out, static_cast<const bf16_t *>(a), static_cast<const bf16_t *>(w),
+                                static_cast<const float *>(dz), dw, db, static_cast<float *>(da), relu_mask ? 1 : 0, ws,
+                                (hipStream_t)stream);
     return fc_backward(N, In, Out, static_cast<const float *>(a), static_cast<const float *>(w), static_cast<const float *>(dz),
                        dw, db, static_cast<float *>(da), relu_mask ? 1 : 0, ws, (hipStream_t)stream);
 }

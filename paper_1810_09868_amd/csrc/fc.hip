@@ -455,4 +455,259 @@ int fc_backward(int N, int In, int Out, const float *a, const float *w, const fl
     return launch_status();
 }
 
+// =========================================================================
+// bf16 operands (activations and weights bf16, dz rounded to bf16, fp32 sums and fp32 results): the
+// matrix-unit numerics of the paper's accelerator applied to the dense layers' backward products.
+//
+// Both products contract over an index that is NOT the contiguous one of its operands in memory
+// (dW: the batch index of dz[n][o] and a[n][i]; dA: the output index of W[o][i]), while
+// v_mfma_f32_32x32x16_bf16 wants eight consecutive contraction indices per lane.  The tiles are staged
+// in LDS as they lie in memory and the fragments are fetched with the LDS transpose read
+// ds_read_b64_tr_b16 (within 16 lanes, lane i receives element i%4 of the 8-byte chunks that lanes
+// i/4, i/4+4, i/4+8, i/4+12 point at: lane s points at contraction index s/4 and channel chunk s%4, so
+// lane i ends up with four consecutive contraction indices of channel i).  LDS rows are 288 bytes
+// (128 channels + 32 bytes of padding): four consecutive rows start 32 bytes apart in the banks.
+// =========================================================================
+namespace {
+
+constexpr int kTrRow = 288;
+
+__device__ __forceinline__ bf16x8 fc_tr_fragment(const char *lds_lo, const char *lds_hi)
+{
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    typedef __attribute__((address_space(3))) s16x4 *lp;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)lds_lo);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)lds_hi);
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// byte offset of this lane's chunk inside a 16-row x 32-channel block of a staged tile
+__device__ __forceinline__ int fc_tr_lane_offset()
+{
+    const int lane = threadIdx.x & 63, G = lane >> 4, i = lane & 15;
+    return (8 * (G >> 1) + (i >> 2)) * kTrRow + (G & 1) * 32 + (i & 3) * 8;
+}
+
+constexpr int kDwRows = 112;  // batch rows per pass of the dW kernel: seven MFMA steps, 2 x 112 x 288 bytes of LDS
+
+// dW = dz^T * a.  Workgroup: 128 (o) x 128 (i) block of dW; wave (wo, wi) owns a 64 x 64 sub-block = 2 x 2 MFMA
+// tiles.  dz is rounded to bf16 while it is staged.
+__global__ __launch_bounds__(256, 2) void fc_dw_bf16_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dz,
+                                                            float *__restrict__ dw, int N, int In, int Out)
+{
+    __shared__ __align__(16) char Ds[kDwRows * kTrRow];
+    __shared__ __align__(16) char As[kDwRows * kTrRow];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, kp = lane >> 5;
+    const int wo = wv & 1, wi = wv >> 1;
+    const int tiles_i = (In + 127) / 128;
+    const int i0 = (blockIdx.x % tiles_i) * 128, o0 = (blockIdx.x / tiles_i) * 128;
+    const int loff = fc_tr_lane_offset();
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[x][y][e] = 0.f;
+
+    for (int n0 = 0; n0 < N; n0 += kDwRows) {
+        __syncthreads();
+        for (int idx = tid; idx < kDwRows * 32; idx += 256) {       // dz: 32 groups of 4 outputs per row
+            const int seg = idx & 31, row = idx >> 5;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (n0 + row < N) v = load_row4(dz + (size_t)(n0 + row) * Out, o0 + seg * 4, Out, (Out & 3) == 0);
+            store4(reinterpret_cast<bf16_t *>(Ds + row * kTrRow) + seg * 4, __uint_as_float(v.x), __uint_as_float(v.y),
+                   __uint_as_float(v.z), __uint_as_float(v.w));
+        }
+        for (int idx = tid; idx < kDwRows * 16; idx += 256) {       // a: 16 segments of 8 inputs per row
+            const int seg = idx & 15, row = idx >> 4;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (n0 + row < N && i0 + seg * 8 < In)                  // In is a multiple of 8
+                v = *reinterpret_cast<const uint4 *>(a + (size_t)(n0 + row) * In + i0 + seg * 8);
+            *reinterpret_cast<uint4 *>(As + row * kTrRow + seg * 16) = v;
+        }
+        __syncthreads();
+        const int steps = min(kDwRows, N - n0 + 15) / 16;
+        for (int s = 0; s < steps; ++s) {
+            bf16x8 df[2], af[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const char *q = Ds + loff + (2 * wo + x) * 64 + 16 * s * kTrRow;
+                df[x] = fc_tr_fragment(q, q + 4 * kTrRow);
+            }
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const char *q = As + loff + (2 * wi + y) * 64 + 16 * s * kTrRow;
+                af[y] = fc_tr_fragment(q, q + 4 * kTrRow);
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[x], af[y], acc[x][y], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) {
+            const int i = i0 + wi * 64 + y * 32 + r;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+                if (o < Out && i < In) dw[(size_t)o * In + i] = acc[x][y][e];
+            }
+        }
+}
+
+// dz fp32 [N][Out] -> bf16 [N][OutP] with zeros in the padding columns
+__global__ void fc_dz_to_bf16_kernel(const float *__restrict__ dz, bf16_t *__restrict__ out, int N, int Out, int OutP)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)N * OutP) return;
+    const int n = (int)(idx / OutP), o = (int)(idx % OutP);
+    out[idx] = o < Out ? f32_to_bf16(dz[(size_t)n * Out + o]) : (bf16_t)0;
+}
+
+struct FcDaBf16Args {
+    const bf16_t *dzb;  // [N][OutP], zeros beyond Out
+    const bf16_t *w;    // [Out][In]
+    float *part;        // [splits][N][In]
+    int N, In, Out, OutP;
+    int tiles_i, tiles_m, o_per_split;
+};
+
+// dA = dz * W.  Workgroup: 128 batch rows x 128 inputs x a range of outputs (the contraction index), 32 at a
+// time.  Wave w owns inputs [32w, 32w+32) and all four 32-row blocks.  The weight rows of the next chunk are
+// requested while the current one is multiplied; dz fragments come straight from the (L2-resident) bf16 copy.
+__global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
+{
+    __shared__ __align__(16) char Ws[32 * kTrRow];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = lane & 31, kp = lane >> 5;
+    int b = blockIdx.x;
+    const int ti = b % p.tiles_i; b /= p.tiles_i;
+    const int tm = b % p.tiles_m; b /= p.tiles_m;
+    const int split = b;
+    const int row0 = tm * 128, i0 = ti * 128;
+    const int o_begin = split * p.o_per_split, o_end = min(o_begin + p.o_per_split, p.Out);
+    const int loff = fc_tr_lane_offset() + wv * 64;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[x][e] = 0.f;
+
+    auto barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    uint4 w_next[2];
+    auto request = [&](int oc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int idx = tid + q * 256;
+            const int seg = idx & 15, row = idx >> 4;
+            w_next[q] = make_uint4(0, 0, 0, 0);
+            if (oc + row < o_end && i0 + seg * 8 < p.In)
+                w_next[q] = *reinterpret_cast<const uint4 *>(p.w + (size_t)(oc + row) * p.In + i0 + seg * 8);
+        }
+    };
+    if (o_begin < o_end) request(o_begin);
+    for (int oc = o_begin; oc < o_end; oc += 32) {
+        barrier();  // the previous chunk's fragment reads are done
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int idx = tid + q * 256;
+            *reinterpret_cast<uint4 *>(Ws + (idx >> 4) * kTrRow + (idx & 15) * 16) = w_next[q];
+        }
+        barrier();  // the staged rows are visible
+        if (oc + 32 < o_end) request(oc + 32);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const char *q = Ws + loff + 16 * ks * kTrRow;
+            const bf16x8 wf = fc_tr_fragment(q, q + 4 * kTrRow);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int n = row0 + x * 32 + r;
+                uint4 d = make_uint4(0, 0, 0, 0);
+                if (n < p.N) d = *reinterpret_cast<const uint4 *>(p.dzb + (size_t)n * p.OutP + oc + 16 * ks + 8 * kp);
+                acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, d), wf, acc[x], 0, 0, 0);
+            }
+        }
+    }
+    const int i = i0 + wv * 32 + r;
+    if (i < p.In) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int n = row0 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+                if (n < p.N) p.part[((size_t)split * p.N + n) * p.In + i] = acc[x][e];
+            }
+    }
+}
+
+// da = (sum over splits) [* (a > 0)], a in bf16
+__global__ void fc_da_bf16_finish_kernel(const float *__restrict__ part, const bf16_t *__restrict__ a, float *__restrict__ da,
+                                         size_t n, int splits, int relu_mask)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(size_t)k * n + i];
+    if (relu_mask && !(bf16_to_f32(a[i]) > 0.f)) s = 0.f;
+    da[i] = s;
+}
+
+void fc_da_bf16_plan(int N, int In, int Out, FcDaBf16Args &a)
+{
+    a.N = N; a.In = In; a.Out = Out;
+    a.OutP = (Out + 31) / 32 * 32 + 32;   // a fragment load may start up to 24 columns before the end of the last chunk
+    a.tiles_i = (In + 127) / 128;
+    a.tiles_m = (N + 127) / 128;
+    const int tiles = a.tiles_i * a.tiles_m;
+    int splits = (768 + tiles - 1) / tiles;
+    const int max_splits = (Out + 63) / 64;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    a.o_per_split = ((Out + splits - 1) / splits + 31) / 32 * 32;
+}
+int fc_da_bf16_splits(const FcDaBf16Args &a) { return (a.Out + a.o_per_split - 1) / a.o_per_split; }
+
+}  // namespace
+
+size_t fc_bwd_bf16_workspace(int N, int In, int Out)
+{
+    FcDaBf16Args a;
+    fc_da_bf16_plan(N, In, Out, a);
+    return round_up((size_t)N * a.OutP * 2, 256) + round_up((size_t)fc_da_bf16_splits(a) * N * In * 4, 256);
+}
+
+// a [N][In] bf16, w [Out][In] bf16, dz [N][Out] fp32 -> dw [Out][In] fp32, db [Out] fp32 (may be null),
+// da [N][In] fp32 (may be null; optionally masked by a > 0).  In must be a multiple of 8.
+int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, const float *dz, float *dw, float *db, float *da,
+                     int relu_mask, void *ws, hipStream_t s)
+{
+    const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
+    hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out);
+    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
+    if (da) {
+        FcDaBf16Args p;
+        fc_da_bf16_plan(N, In, Out, p);
+        const int splits = fc_da_bf16_splits(p);
+        bf16_t *dzb = static_cast<bf16_t *>(ws);
+        const size_t nd = (size_t)N * p.OutP;
+        hipLaunchKernelGGL(fc_dz_to_bf16_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, dz, dzb, N, Out, p.OutP);
+        p.dzb = dzb; p.w = w;
+        p.part = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up(nd * 2, 256));
+        hipLaunchKernelGGL(fc_da_bf16_kernel, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
+        const size_t n = (size_t)N * In;
+        hipLaunchKernelGGL(fc_da_bf16_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.part, a, da, n,
+                           splits, relu_mask);
+    }
+    return launch_status();
+}
+
 }  // namespace vgg

@@ -284,7 +284,7 @@ def _bf16_step_from_single_op_calls(inp, N, H, W, hidden, classes):
         dw = torch.empty((o, i), device="cuda")
         db = torch.empty((o,), device="cuda")
         da = torch.empty((N, i), device="cuda")
-        B.vgg_fc_bwd(B.F32, N, i, o, a_in[l].float(), fcw32[l], dz, dw, db, da, 1, ws(B.vgg_fc_bwd_workspace_bytes(B.F32, N, i, o)))
+        B.vgg_fc_bwd(B.BF16, N, i, o, a_in[l], fcw32[l].to(bf), dz, dw, db, da, 1, ws(B.vgg_fc_bwd_workspace_bytes(B.BF16, N, i, o)))
         g["fc_w"][l], g["fc_b"][l] = dw, db
         dz = da
     g["fc_w"][0] = g["fc_w"][0].view(hidden, h * w, 512).permute(0, 2, 1).reshape(hidden, flat).contiguous()

@@ -266,26 +266,31 @@ def test_fc_forward(dtype, shape):
         assert max_rel_err(z.float().cpu().numpy(), ref) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200)])
-def test_fc_backward(shape):
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200), (113, 160, 33), (250, 96, 72)])
+def test_fc_backward(dtype, shape):
+    # bf16: a and w are bf16, dz fp32 (rounded to bf16 inside, except for db); all results fp32
     N, In, Out = shape
     rng = np.random.default_rng(sum(shape) + 5)
     a = rng.standard_normal((N, In)).astype(np.float32)
     w = (rng.standard_normal((Out, In)) * np.sqrt(2.0 / In)).astype(np.float32)
     dz = rng.standard_normal((N, Out)).astype(np.float32)
     dw_ref, db_ref, da_ref = R.fc_bwd(a, w, dz)
-    dw = torch.empty((Out, In), device="cuda")
+    dw = torch.full((Out, In), float("nan"), device="cuda")
     db = torch.empty((Out,), device="cuda")
-    da = torch.empty((N, In), device="cuda")
-    ws = ws_bytes(B.vgg_fc_bwd_workspace_bytes(B.F32, N, In, Out))
-    B.vgg_fc_bwd(B.F32, N, In, Out, dev(a), dev(w), dev(dz), dw, db, da, 0, ws)
+    da = torch.full((N, In), float("nan"), device="cuda")
+    ws = ws_bytes(B.vgg_fc_bwd_workspace_bytes(dtype, N, In, Out))
+    ad, wd = dev(a, TDT[dtype]), dev(w, TDT[dtype])
+    B.vgg_fc_bwd(dtype, N, In, Out, ad, wd, dev(dz), dw, db, da, 0, ws)
     torch.cuda.synchronize()
-    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[B.F32]
-    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[B.F32]
-    assert max_rel_err(da.cpu().numpy(), da_ref) <= TOL[B.F32]
-    B.vgg_fc_bwd(B.F32, N, In, Out, dev(a), dev(w), dev(dz), dw, None, da, 1, ws)
+    assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[dtype]
+    assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[B.F32]         # a plain fp32 sum in both
+    assert max_rel_err(da.cpu().numpy(), da_ref) <= TOL[dtype]
+    B.vgg_fc_bwd(dtype, N, In, Out, ad, wd, dev(dz), dw, None, da, 1, ws)
     torch.cuda.synchronize()
-    assert max_rel_err(da.cpu().numpy(), da_ref * (a > 0)) <= TOL[B.F32]
+    assert max_rel_err(da.cpu().numpy(), da_ref * (ad.float().cpu().numpy() > 0)) <= TOL[dtype]
+    with pytest.raises(B.VggError):
+        B.vgg_fc_bwd(dtype, N, In, Out, ad, wd, dev(dz), dw, None, da, 1, None)
 
 
 @pytest.mark.parametrize("shape", [(100, 1000), (2, 10), (5, 64), (3, 129)])
