@@ -212,7 +212,8 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
  * da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by (a[n,i] > 0)
  * when relu_mask != 0 (ReLU backward of the producer of a).  a and w are in
  * `dtype`; dz, dw, db and da are always fp32.  VGG_BF16: dz is rounded to
- * bf16 where it enters a product (not for db), sums are fp32. */
+ * bf16 where it enters a product (not for db), sums are fp32.  The workspace
+ * is needed when da is requested and, for VGG_BF16, always. */
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz,
                float *dw, float *db, void *da, int relu_mask, void *ws, size_t ws_bytes,

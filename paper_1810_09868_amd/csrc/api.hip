@@ -627,7 +627,8 @@ int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, 
     if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(w) || !aligned16(dz) || !aligned16(dw) || (da && !aligned16(da)) || (ws && !aligned16(ws)))
         return VGG_ERR_ALIGN;
-    if (da && (!ws || ws_bytes < vgg_fc_bwd_workspace_bytes(dtype, N, In, Out))) return VGG_ERR_WORKSPACE;
+    // (bf16: the rounded copy of dz lives in the workspace, so it is needed even without da)
+    if ((da || dtype == VGG_BF16) && (!ws || ws_bytes < vgg_fc_bwd_workspace_bytes(dtype, N, In, Out))) return VGG_ERR_WORKSPACE;
     if (dtype == VGG_BF16)
         return fc_backward_bf16(N, In, Out, static_cast<const bf16_t *>(a), static_cast<const bf16_t *>(w),
                                 static_cast<const float *>(dz), dw, db, static_cast<float *>(da), relu_mask ? 1 : 0, ws,

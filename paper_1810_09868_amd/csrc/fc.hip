@@ -490,12 +490,12 @@ __device__ __forceinline__ int fc_tr_lane_offset()
     return (8 * (G >> 1) + (i >> 2)) * kTrRow + (G & 1) * 32 + (i & 3) * 8;
 }
 
-constexpr int kDwRows = 112;  // batch rows per pass of the dW kernel: seven MFMA steps, 2 x 112 x 288 bytes of LDS
+constexpr int kDwRows = 64;   // batch rows per pass of the dW kernel: four MFMA steps, 2 x 64 x 288 bytes of LDS (four workgroups per CU)
 
 // dW = dz^T * a.  Workgroup: 128 (o) x 128 (i) block of dW; wave (wo, wi) owns a 64 x 64 sub-block = 2 x 2 MFMA
-// tiles.  dz is rounded to bf16 while it is staged.
-__global__ __launch_bounds__(256, 2) void fc_dw_bf16_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dz,
-                                                            float *__restrict__ dw, int N, int In, int Out)
+// tiles.  dzb: dz rounded to bf16, rows of OutP >= Out + 7 elements (a multiple of 8), zeros beyond Out.
+__global__ __launch_bounds__(256) void fc_dw_bf16_kernel(const bf16_t *__restrict__ a, const bf16_t *__restrict__ dzb,
+                                                            float *__restrict__ dw, int N, int In, int Out, int OutP)
 {
     __shared__ __align__(16) char Ds[kDwRows * kTrRow];
     __shared__ __align__(16) char As[kDwRows * kTrRow];
@@ -516,12 +516,12 @@ __global__ __launch_bounds__(256, 2) void fc_dw_bf16_kernel(const bf16_t *__rest
 
     for (int n0 = 0; n0 < N; n0 += kDwRows) {
         __syncthreads();
-        for (int idx = tid; idx < kDwRows * 32; idx += 256) {       // dz: 32 groups of 4 outputs per row
-            const int seg = idx & 31, row = idx >> 5;
+        for (int idx = tid; idx < kDwRows * 16; idx += 256) {       // dz: 16 segments of 8 outputs per row
+            const int seg = idx & 15, row = idx >> 4;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (n0 + row < N) v = load_row4(dz + (size_t)(n0 + row) * Out, o0 + seg * 4, Out, (Out & 3) == 0);
-            store4(reinterpret_cast<bf16_t *>(Ds + row * kTrRow) + seg * 4, __uint_as_float(v.x), __uint_as_float(v.y),
-                   __uint_as_float(v.z), __uint_as_float(v.w));
+            if (n0 + row < N && o0 + seg * 8 < Out)
+                v = *reinterpret_cast<const uint4 *>(dzb + (size_t)(n0 + row) * OutP + o0 + seg * 8);
+            *reinterpret_cast<uint4 *>(Ds + row * kTrRow + seg * 16) = v;
         }
         for (int idx = tid; idx < kDwRows * 16; idx += 256) {       // a: 16 segments of 8 inputs per row
             const int seg = idx & 15, row = idx >> 4;
@@ -582,7 +582,7 @@ struct FcDaBf16Args {
 
 // dA = dz * W.  Workgroup: 128 batch rows x 128 inputs x a range of outputs (the contraction index), 32 at a
 // time.  Wave w owns inputs [32w, 32w+32) and all four 32-row blocks.  The weight rows of the next chunk are
-// requested while the current one is multiplied; dz fragments come straight from the (L2-resident) bf16 copy.
+// and the dz fragments (straight from the L2-resident bf16 copy) are requested while the current one is multiplied.
 __global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
 {
     __shared__ __align__(16) char Ws[32 * kTrRow];
@@ -603,7 +603,7 @@ __global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
         for (int e = 0; e < 16; ++e) acc[x][e] = 0.f;
 
     auto barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
-    uint4 w_next[2];
+    uint4 w_next[2], d_next[2][4];
     auto request = [&](int oc) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -613,6 +613,14 @@ __global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
             if (oc + row < o_end && i0 + seg * 8 < p.In)
                 w_next[q] = *reinterpret_cast<const uint4 *>(p.w + (size_t)(oc + row) * p.In + i0 + seg * 8);
         }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int n = row0 + x * 32 + r;
+                d_next[ks][x] = make_uint4(0, 0, 0, 0);
+                if (n < p.N) d_next[ks][x] = *reinterpret_cast<const uint4 *>(p.dzb + (size_t)n * p.OutP + oc + 16 * ks + 8 * kp);
+            }
     };
     if (o_begin < o_end) request(o_begin);
     for (int oc = o_begin; oc < o_end; oc += 32) {
@@ -622,6 +630,11 @@ __global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
             const int idx = tid + q * 256;
             *reinterpret_cast<uint4 *>(Ws + (idx >> 4) * kTrRow + (idx & 15) * 16) = w_next[q];
         }
+        uint4 d_cur[2][4];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) d_cur[ks][x] = d_next[ks][x];
         barrier();  // the staged rows are visible
         if (oc + 32 < o_end) request(oc + 32);
 #pragma unroll
@@ -629,12 +642,8 @@ __global__ __launch_bounds__(256) void fc_da_bf16_kernel(FcDaBf16Args p)
             const char *q = Ws + loff + 16 * ks * kTrRow;
             const bf16x8 wf = fc_tr_fragment(q, q + 4 * kTrRow);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int n = row0 + x * 32 + r;
-                uint4 d = make_uint4(0, 0, 0, 0);
-                if (n < p.N) d = *reinterpret_cast<const uint4 *>(p.dzb + (size_t)n * p.OutP + oc + 16 * ks + 8 * kp);
-                acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, d), wf, acc[x], 0, 0, 0);
-            }
+            for (int x = 0; x < 4; ++x)
+                acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, d_cur[ks][x]), wf, acc[x], 0, 0, 0);
         }
     }
     const int i = i0 + wv * 32 + r;
@@ -690,16 +699,16 @@ size_t fc_bwd_bf16_workspace(int N, int In, int Out)
 int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, const float *dz, float *dw, float *db, float *da,
                      int relu_mask, void *ws, hipStream_t s)
 {
+    FcDaBf16Args p;
+    fc_da_bf16_plan(N, In, Out, p);
+    bf16_t *dzb = static_cast<bf16_t *>(ws);
+    const size_t nd = (size_t)N * p.OutP;
+    hipLaunchKernelGGL(fc_dz_to_bf16_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, dz, dzb, N, Out, p.OutP);
     const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
-    hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out);
+    hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dzb, dw, N, In, Out, p.OutP);
     if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
     if (da) {
-        FcDaBf16Args p;
-        fc_da_bf16_plan(N, In, Out, p);
         const int splits = fc_da_bf16_splits(p);
-        bf16_t *dzb = static_cast<bf16_t *>(ws);
-        const size_t nd = (size_t)N * p.OutP;
-        hipLaunchKernelGGL(fc_dz_to_bf16_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, dz, dzb, N, Out, p.OutP);
         p.dzb = dzb; p.w = w;
         p.part = reinterpret_cast<float *>(static_cast<char *>(ws) + round_up(nd * 2, 256));
         hipLaunchKernelGGL(fc_da_bf16_kernel, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
