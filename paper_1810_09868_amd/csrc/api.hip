@@ -346,22 +346,37 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
         return;
     }
-    // master <- master - lr * gradient, working copy <- master (bf16 weights, fp32 biases), tensor by tensor
-    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
-        VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)9 * kConvCh[l][1] * P.cinp[l], F(pm + Pm.conv_w[l]), F(gr + Pm.conv_w[l]),
-                                                 c->lr, pk + P.conv_w[l], VGG_BF16, s));
-        VGG_STEP(rec, K_OTHER, sgd_update_master(kConvCh[l][1], F(pm + Pm.conv_b[l]), F(gr + Pm.conv_b[l]), c->lr,
-                                                 pk + P.conv_b[l], VGG_F32, s));
-    }
-    for (int l = 0; l < VGG19_NUM_FC; ++l) {
-        VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)P.fc_in[l] * P.fc_out[l], F(pm + Pm.fc_w[l]), F(gr + Pm.fc_w[l]), c->lr,
-                                                 pk + P.fc_w[l], VGG_BF16, s));
-    }
-    // (bias counts need not be multiples of four: the dense biases take the plain kernels)
-    for (int l = 0; l < VGG19_NUM_FC; ++l) {
-        VGG_STEP(rec, K_OTHER, sgd_update(P.fc_out[l], F(pm + Pm.fc_b[l]), F(gr + Pm.fc_b[l]), c->lr, s));
-        VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], pm + Pm.fc_b[l], pk + P.fc_b[l], s));
-    }
+    // master <- master - lr * gradient, working copy <- master (bf16 weights, fp32 biases).  Inside the two
+    // blocks the tensors follow each other in the same order; where a group of tensors is laid out
+    // proportionally (bf16 offsets exactly half the fp32 ones, which the 256-byte alignment gives whenever
+    // every bf16 tensor size is a multiple of 256 bytes) the whole group, gaps included, takes one launch.
+    auto group = [&](size_t m_first, size_t m_end, size_t w_first, size_t w_end, int copy_dtype) {
+        const size_t n = (m_end - m_first) / 4;
+        if ((w_end - w_first) * (copy_dtype == VGG_BF16 ? 2 : 1) != m_end - m_first || n % 4) return false;
+        VGG_STEP(rec, K_OTHER, sgd_update_master(n, F(pm + m_first), F(gr + m_first), c->lr, pk + w_first, copy_dtype, s));
+        return true;
+    };
+    bool conv_prop = true, fc_prop = true;
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) conv_prop = conv_prop && Pm.conv_w[l] == 2 * P.conv_w[l];
+    for (int l = 0; l < VGG19_NUM_FC; ++l) fc_prop = fc_prop && Pm.fc_w[l] - Pm.fc_w[0] == 2 * (P.fc_w[l] - P.fc_w[0]);
+    if (!(conv_prop && group(Pm.conv_w[0], Pm.conv_b[0], P.conv_w[0], P.conv_b[0], VGG_BF16)))
+        for (int l = 0; l < VGG19_NUM_CONV; ++l)
+            VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)9 * kConvCh[l][1] * P.cinp[l], F(pm + Pm.conv_w[l]),
+                                                     F(gr + Pm.conv_w[l]), c->lr, pk + P.conv_w[l], VGG_BF16, s));
+    if (!group(Pm.conv_b[0], Pm.fc_w[0], P.conv_b[0], P.fc_w[0], VGG_F32))
+        for (int l = 0; l < VGG19_NUM_CONV; ++l)
+            VGG_STEP(rec, K_OTHER, sgd_update_master(kConvCh[l][1], F(pm + Pm.conv_b[l]), F(gr + Pm.conv_b[l]), c->lr,
+                                                     pk + P.conv_b[l], VGG_F32, s));
+    if (!(fc_prop && group(Pm.fc_w[0], Pm.fc_b[0], P.fc_w[0], P.fc_b[0], VGG_BF16)))
+        for (int l = 0; l < VGG19_NUM_FC; ++l)
+            VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)P.fc_in[l] * P.fc_out[l], F(pm + Pm.fc_w[l]), F(gr + Pm.fc_w[l]),
+                                                     c->lr, pk + P.fc_w[l], VGG_BF16, s));
+    if (!group(Pm.fc_b[0], Pm.total, P.fc_b[0], P.total, VGG_F32))
+        for (int l = 0; l < VGG19_NUM_FC; ++l) {
+            // (bias counts need not be multiples of four: the plain kernels)
+            VGG_STEP(rec, K_OTHER, sgd_update(P.fc_out[l], F(pm + Pm.fc_b[l]), F(gr + Pm.fc_b[l]), c->lr, s));
+            VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], pm + Pm.fc_b[l], pk + P.fc_b[l], s));
+        }
 }
 
 bool params_ok(const vgg19_params *p)
