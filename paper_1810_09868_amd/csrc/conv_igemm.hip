@@ -32,6 +32,7 @@ constexpr int kEpiBytes = 32 * kEpiRow;   // per wave
 constexpr int kMaxAHaloSegsPerBlock = 1536;  // 16-byte halo segments (384 rows) prefetched through registers
 constexpr int kDmaHaloRows = 384;            // halo rows of the direct-to-LDS kernel: 2 workgroups of 74 KB per CU
 constexpr int kDmaHaloRowsBig = 448;         // ... and of its variant for tiles that straddle images (78 KB)
+constexpr int kDmaHaloRowsHalf = 192;        // ... and of the 128-pixel tiles (38 KB: four workgroups per CU)
 
 struct ConvArgs {
     const char *x;      // [M][CinP] elements of T
@@ -675,7 +676,7 @@ __global__ __launch_bounds__(256) void conv_split_finish_kernel(const float *__r
 // Which kernel a shape gets, and whether its contraction is split over several workgroups per tile.
 struct ConvPlan {
     TileGeom g;
-    bool narrow, dma, dma_big;
+    bool narrow, dma, dma_big, half;
     int ksplit, kchunks;
 };
 
@@ -708,6 +709,14 @@ static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bo
         if (want > chunks / 2) want = chunks / 2;
         c.kchunks = (chunks + want - 1) / want;
         c.ksplit = (chunks + c.kchunks - 1) / c.kchunks;
+    }
+    // fp32, 64-wide tiles, a launch of only a few workgroups per CU (the 14x14 layers at batch 100: 616
+    // on 768 slots): 128-pixel tiles double the count and even out the load, +15 % there.  (bf16 loses
+    // 5 % the same way: its workgroups are short enough that the smaller tile's overhead weighs more.)
+    c.half = false;
+    if (dtype == VGG_F32 && c.narrow && (c.dma || c.dma_big) && !pool && c.ksplit == 1 && total >= 256 && total < 2048) {
+        const TileGeom h = make_tile_geom(N, H, W, 128);
+        if (h.S <= kDmaHaloRowsHalf) { c.g = h; c.half = true; }
     }
     return c;
 }
@@ -750,7 +759,9 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
     const TileGeom &g = c.g;
     int rc;
     if (dtype == VGG_F32) {
-        if (dma)
+        if (c.half)
+            rc = launch_conv_dma<float, 128, 64, 4, 1, kDmaHaloRowsHalf>(a, g, stream);
+        else if (dma)
             rc = narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
                         : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
         else if (dma_big)
