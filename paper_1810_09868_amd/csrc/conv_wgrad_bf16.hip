@@ -149,23 +149,42 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         __syncthreads();
         if (tile + 1 < t_end) issue(tile + 1, smem + (buf ^ 1) * kBuf);
         const char *B = smem + buf * kBuf;
+        // Fragments are requested one MFMA group ahead of their use (the LDS latency of a transpose read
+        // is longer than the two MFMAs a fragment feeds, and only two waves share a SIMD).
+        auto g_frag = [&](int s, int c) __attribute__((always_inline)) {
+            return tr_fragment(B + g_off + c * 64 + (16 * s) * kRow, B + g_off + c * 64 + (16 * s + 4) * kRow);
+        };
+        auto x_frag = [&](int s, int t) __attribute__((always_inline)) {
+            const int kh = (T0 + t) / 3, kw = (T0 + t) % 3;
+            const int ro = ((s + kh) * kHW + kw) * kRow;
+            return tr_fragment(B + x_off + ro, B + x_off + ro + 4 * kRow);
+        };
+        bf16x8 gf[2], gf_next[2], xf, xf_next;
+        gf_next[0] = g_frag(0, 0);
+        gf_next[1] = g_frag(0, 1);
+        xf_next = x_frag(0, 0);
 #pragma unroll
         for (int s = 0; s < kTH; ++s) {
-            bf16x8 gf[2];
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-                gf[c] = tr_fragment(B + g_off + c * 64 + (16 * s) * kRow, B + g_off + c * 64 + (16 * s + 4) * kRow);
+            gf[0] = gf_next[0];
+            gf[1] = gf_next[1];
             if (DB) {
 #pragma unroll
                 for (int c = 0; c < 2; ++c) accb[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], ones, accb[c], 0, 0, 0);
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const int kh = (T0 + t) / 3, kw = (T0 + t) % 3;
-                const int ro = ((s + kh) * kHW + kw) * kRow;
-                const bf16x8 xf = tr_fragment(B + x_off + ro, B + x_off + ro + 4 * kRow);
+                xf = xf_next;
+                if (t + 1 < NT) {
+                    xf_next = x_frag(s, t + 1);
+                } else if (s + 1 < kTH) {
+                    gf_next[0] = g_frag(s + 1, 0);
+                    gf_next[1] = g_frag(s + 1, 1);
+                    xf_next = x_frag(s + 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the MFMAs they overlap with
 #pragma unroll
                 for (int c = 0; c < 2; ++c) acc[c][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], xf, acc[c][t], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
