@@ -111,7 +111,7 @@ struct WsLayout {
     size_t convpart;                   // partial sums of convolutions whose contraction is split
     // training only
     size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
-    size_t a32, dflat32;               // bf16 training: fp32 gradient with respect to the flattened pool output (a32 unused)
+    size_t dflat32;                    // bf16 training: fp32 gradient with respect to the flattened pool output
     size_t total;
     int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
 };
@@ -174,7 +174,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         if (s > cpart) cpart = s;
     }
     L.convpart = b.take(cpart);
-    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = L.a32 = L.dflat32 = 0;
+    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = L.dflat32 = 0;
     if (training) {
         L.dlogits = b.take(N * c->classes * 4);
         L.dz2 = b.take(N * c->fc_hidden * 4);

@@ -19,8 +19,6 @@
 // operand of one v_mfma_f32_32x32x16_bf16; for fp32 the four elements feed
 // four v_mfma_f32_32x32x2_f32 (any fixed pairing of k indices between A and B
 // is a valid contraction order).
-#include <cstdlib>
-
 #include "common.h"
 
 namespace vgg {
@@ -684,17 +682,12 @@ static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bo
 {
     ConvPlan c;
     c.narrow = Cout <= 64;
-    // For A/B measurements: VGG_CONV_VARIANT=1 forces the register-staged kernel, 2 the 64-wide
-    // column tiles, 3 the 128-wide ones, 4 keeps every contraction in one workgroup.
-    static const int variant = getenv("VGG_CONV_VARIANT") ? atoi(getenv("VGG_CONV_VARIANT")) : 0;
     c.g = make_tile_geom(N, H, W, 256);
-    c.dma = variant != 1 && c.g.S <= kDmaHaloRows;
-    c.dma_big = variant != 1 && !c.dma && c.g.S <= kDmaHaloRowsBig;
+    c.dma = c.g.S <= kDmaHaloRows;
+    c.dma_big = !c.dma && c.g.S <= kDmaHaloRowsBig;
     // Too few 256x128 tiles to give every CU two workgroups (the 14x14 layers): 64-wide column tiles
     // double the workgroup count and three of them fit on a CU.
     if (c.g.ntiles * ((Cout + 127) / 128) < 512) c.narrow = true;
-    if (variant == 2) c.narrow = true;
-    if (variant == 3) c.narrow = false;
     // Small batches: fewer tiles than CUs, each walking the whole contraction alone.  Then several
     // workgroups share a tile, each taking a range of channel chunks (at least two), and a second
     // kernel adds their partial sums.
@@ -703,7 +696,7 @@ static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bo
     c.ksplit = 1; c.kchunks = chunks;
     // Measured: pays when at most half the CUs would have a workgroup and a tile's contraction is
     // long enough (a bf16 chunk takes a quarter of the time of an fp32 one).
-    if (variant != 4 && (c.dma || c.dma_big) && !pool && Cout % 4 == 0 && total <= 128 &&
+    if ((c.dma || c.dma_big) && !pool && Cout % 4 == 0 && total <= 128 &&
         chunks >= (dtype == VGG_BF16 ? 8 : 4)) {
         int want = (512 + total - 1) / total;   // two workgroups per CU
         if (want > chunks / 2) want = chunks / 2;
