@@ -27,6 +27,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? VGG_OK : V
 // fp32 -> bf16, round to nearest even: the hardware conversion (v_cvt_pk_bf16_f32), one
 // instruction instead of a dozen.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// The gradient step on one value, rounded once; every kernel that takes the step uses this form, so a
+// step fused into a gradient kernel and a separate update leave identical parameters.
+__device__ __forceinline__ float sgd_step(float theta, float grad, float lr) { return __builtin_fmaf(-lr, grad, theta); }
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((unsigned int)h) << 16); }
 
 template <typename T> struct Elem;

@@ -162,10 +162,10 @@ __global__ void sgd_kernel(float *__restrict__ theta, const float *__restrict__ 
     if (i < n4) {
         f32x4 t = reinterpret_cast<f32x4 *>(theta)[i];
         const f32x4 g = reinterpret_cast<const f32x4 *>(grad)[i];
-        t.x -= lr * g.x; t.y -= lr * g.y; t.z -= lr * g.z; t.w -= lr * g.w;
+        t.x = sgd_step(t.x, g.x, lr); t.y = sgd_step(t.y, g.y, lr); t.z = sgd_step(t.z, g.z, lr); t.w = sgd_step(t.w, g.w, lr);
         reinterpret_cast<f32x4 *>(theta)[i] = t;
     } else if (i == n4) {
-        for (size_t k = n4 * 4; k < n; ++k) theta[k] -= lr * grad[k];
+        for (size_t k = n4 * 4; k < n; ++k) theta[k] = sgd_step(theta[k], grad[k], lr);
     }
 }
 
@@ -186,7 +186,7 @@ __global__ void sgd_master_kernel(float *__restrict__ theta, const float *__rest
     if (i >= n4) return;
     f32x4 t = reinterpret_cast<f32x4 *>(theta)[i];
     const f32x4 g = reinterpret_cast<const f32x4 *>(grad)[i];
-    t.x -= lr * g.x; t.y -= lr * g.y; t.z -= lr * g.z; t.w -= lr * g.w;
+    t.x = sgd_step(t.x, g.x, lr); t.y = sgd_step(t.y, g.y, lr); t.z = sgd_step(t.z, g.z, lr); t.w = sgd_step(t.w, g.w, lr);
     reinterpret_cast<f32x4 *>(theta)[i] = t;
     store4(copy + i * 4, t.x, t.y, t.z, t.w);
 }

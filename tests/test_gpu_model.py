@@ -491,6 +491,35 @@ def test_full_vgg19_train_step_batch100_is_mean_of_chunks(dtype):
             assert max_rel_err(upd, -0.01 * gb[k][l].numpy()) <= 1e-3, (k, l)
 
 
+@pytest.mark.parametrize("size", ["tiny", "224"])
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_train_step_without_gradient_output_leaves_the_same_parameters(dtype, size):
+    # A caller that does not ask for the gradients gets the dense layers' update inside their
+    # weight-gradient kernels (the gradient is never written); the parameters, master and working
+    # copy, must come out bit-identical to the path that writes the gradients and updates
+    # afterwards -- over two steps, so that the second runs on the first's updated weights.
+    if size == "tiny":
+        inp, shape = synth.tiny_config(seed=9), (2, 32, 32, 512, 10)
+    else:
+        inp, shape = synth.full_config(2, seed=9, with_labels=True), (2, 224, 224, 4096, 1000)
+    plain = Vgg19(dtype, *shape, lr=0.01, training=True)
+    fused = Vgg19(dtype, *shape, lr=0.01, training=True)
+    for m in (plain, fused):
+        m.pack(inp.conv_w, inp.conv_b, inp.fc_w, inp.fc_b)
+    assert torch.equal(plain.packed, fused.packed)
+    x, lab = dev(inp.x), dev(inp.labels)
+    for step in range(2):
+        plain.train_step(x, lab, want_grads=True)
+        fused.train_step(x, lab, want_grads=False)
+        torch.cuda.synchronize()
+        assert torch.equal(plain.loss, fused.loss), step
+        assert torch.equal(plain.logits, fused.logits), step
+        assert torch.equal(plain.packed, fused.packed), step
+    # and the step did move the dense weights
+    before = np.asarray(inp.fc_w[2], dtype=np.float32)
+    assert np.abs(fused.unpack()["fc_w"][2] - before).max() > 0
+
+
 def test_training_loop_as_one_graph_matches_eager_steps():
     # K steps recorded once and replayed as a single launch must leave exactly the parameters that K eager
     # steps leave (every kernel is deterministic); replayed several times, with eager work and
