@@ -26,6 +26,10 @@
 // barrier per tile.  The block writes partial sums; a second kernel adds the partials of all
 // splits in a fixed order, so the result does not depend on scheduling.  The bias gradient comes
 // from two extra MFMAs per step against a fragment of ones, in the blocks of the first ci tile.
+//
+// At most 32 input channels (the first layer): the second ci half would be padding.  The two waves of
+// a tap group then both take the first half and alternate over the patch rows instead, and write
+// their sums as two separate partials.
 #include "common.h"
 
 namespace vgg {
@@ -59,6 +63,7 @@ struct WgradBf16Args {
     int N, H, W, CinP, Cout;
     int tiles_co, tiles_ci, splits, tiles_per_split, ntiles;
     int tiles_w, tiles_hw;
+    int narrow;       // CinP <= 32: the waves of a tap group split the patch rows, not the channels
     FastDiv dTilesW, dTilesHW;
 };
 
@@ -71,12 +76,14 @@ __device__ __forceinline__ bf16x8 tr_fragment(const char *lds_lo, const char *ld
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// Taps [T0, T0 + NT) of one wave.  DB: this wave also sums g over the pixels.
-template <int T0, int NT, bool DB>
+// Taps [T0, T0 + NT) of one wave.  DB: this wave also sums g over the pixels.  NARROW: see above.
+template <int T0, int NT, bool DB, bool NARROW>
 __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *smem, int tco, int tci, int split)
 {
+    constexpr int NS = NARROW ? kTH / 2 : kTH;               // MFMA steps of this wave per tile
+    constexpr int SS = NARROW ? 2 : 1;                       // patch rows between them
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wi = wv & 1;                                   // ci half of this wave
+    const int wi = wv & 1;                                   // ci half of this wave (NARROW: its first patch row)
     const int co0 = tco * kCO, ci0 = tci * kCI;
 
     f32x16 acc[2][NT];
@@ -131,8 +138,8 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
     // read) of a patch row and at the 8-byte chunk i & 3 of the 32-byte run G & 1 of a 32-channel tile.
     const int G = lane >> 4, i = lane & 15;
     const int lane_off = (8 * (G >> 1) + (i >> 2)) * kRow + (G & 1) * 32 + (i & 3) * 8;
-    const int g_off = lane_off;                              // + co tile * 64 + (16 s + 4 h) * kRow
-    const int x_off = kGBytes + lane_off + wi * 64;          // + ((s + kh) * 18 + kw + 4 h) * kRow
+    const int g_off = lane_off + (NARROW ? wi * kTW * kRow : 0);                    // + co tile * 64 + (16 s + 4 h) * kRow
+    const int x_off = kGBytes + lane_off + (NARROW ? wi * kHW * kRow : wi * 64);    // + ((s + kh) * 18 + kw + 4 h) * kRow
 
     const int t_begin = split * p.tiles_per_split;
     const int t_end = min(t_begin + p.tiles_per_split, p.ntiles);
@@ -152,11 +159,11 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         // Fragments are requested one MFMA group ahead of their use (the LDS latency of a transpose read
         // is longer than the two MFMAs a fragment feeds, and only two waves share a SIMD).
         auto g_frag = [&](int s, int c) __attribute__((always_inline)) {
-            return tr_fragment(B + g_off + c * 64 + (16 * s) * kRow, B + g_off + c * 64 + (16 * s + 4) * kRow);
+            return tr_fragment(B + g_off + c * 64 + (16 * SS * s) * kRow, B + g_off + c * 64 + (16 * SS * s + 4) * kRow);
         };
         auto x_frag = [&](int s, int t) __attribute__((always_inline)) {
             const int kh = (T0 + t) / 3, kw = (T0 + t) % 3;
-            const int ro = ((s + kh) * kHW + kw) * kRow;
+            const int ro = ((SS * s + kh) * kHW + kw) * kRow;
             return tr_fragment(B + x_off + ro, B + x_off + ro + 4 * kRow);
         };
         bf16x8 gf[2], gf_next[2], xf, xf_next;
@@ -164,7 +171,7 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         gf_next[1] = g_frag(0, 1);
         xf_next = x_frag(0, 0);
 #pragma unroll
-        for (int s = 0; s < kTH; ++s) {
+        for (int s = 0; s < NS; ++s) {
             gf[0] = gf_next[0];
             gf[1] = gf_next[1];
             if (DB) {
@@ -176,7 +183,7 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
                 xf = xf_next;
                 if (t + 1 < NT) {
                     xf_next = x_frag(s, t + 1);
-                } else if (s + 1 < kTH) {
+                } else if (s + 1 < NS) {
                     gf_next[0] = g_frag(s + 1, 0);
                     gf_next[1] = g_frag(s + 1, 1);
                     xf_next = x_frag(s + 1, 0);
@@ -191,7 +198,8 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
 
     // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (co), column l%32 (ci)
     const int r = lane & 31, kp = lane >> 5;
-    const int ci = ci0 + wi * 32 + r;
+    const int ci = ci0 + (NARROW ? 0 : wi * 32) + r;
+    if (NARROW) split = 2 * split + wi;                      // this wave's own partial
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -226,9 +234,15 @@ __global__ __launch_bounds__(kNW * 64, 2) void conv3x3_wgrad_bf16_kernel(WgradBf
     // (wave-uniform branches: all bodies execute the same sequence of barriers)
     const int group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (group == 0) wgrad_bf16_body<0, 5, false>(p, smem, tco, tci, split);
-    else if (p.dbpart && tci == 0 && wave == 2) wgrad_bf16_body<5, 4, true>(p, smem, tco, tci, split);
-    else wgrad_bf16_body<5, 4, false>(p, smem, tco, tci, split);
+    if (p.narrow) {
+        if (group == 0) wgrad_bf16_body<0, 5, false, true>(p, smem, tco, tci, split);
+        else if (p.dbpart) wgrad_bf16_body<5, 4, true, true>(p, smem, tco, tci, split);   // each wave sums g over its own rows
+        else wgrad_bf16_body<5, 4, false, true>(p, smem, tco, tci, split);
+        return;
+    }
+    if (group == 0) wgrad_bf16_body<0, 5, false, false>(p, smem, tco, tci, split);
+    else if (p.dbpart && tci == 0 && wave == 2) wgrad_bf16_body<5, 4, true, false>(p, smem, tco, tci, split);
+    else wgrad_bf16_body<5, 4, false, false>(p, smem, tco, tci, split);
 }
 
 void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
@@ -247,7 +261,10 @@ void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
     if (splits < 1) splits = 1;
     a.tiles_per_split = (a.ntiles + splits - 1) / splits;
     a.splits = (a.ntiles + a.tiles_per_split - 1) / a.tiles_per_split;
+    a.narrow = CinP <= kCI / 2;
 }
+// partial results the reduction adds up
+inline int wgrad_bf16_partials(const WgradBf16Args &a) { return a.narrow ? 2 * a.splits : a.splits; }
 
 }  // namespace
 
@@ -255,7 +272,8 @@ size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 {
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
-    return round_up((size_t)a.splits * 9 * Cout * CinP * 4, 256) + round_up((size_t)a.splits * Cout * 4, 256);
+    const size_t np = (size_t)wgrad_bf16_partials(a);
+    return round_up(np * 9 * Cout * CinP * 4, 256) + round_up(np * Cout * 4, 256);
 }
 
 // x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
@@ -270,12 +288,13 @@ int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x,
     a.x = x; a.g = g;
     const size_t nw = (size_t)9 * Cout * CinP;
     a.part = static_cast<float *>(ws);
-    a.dbpart = db ? reinterpret_cast<float *>(static_cast<char *>(ws) + round_up((size_t)a.splits * nw * 4, 256)) : nullptr;
+    const int np = wgrad_bf16_partials(a);
+    a.dbpart = db ? reinterpret_cast<float *>(static_cast<char *>(ws) + round_up((size_t)np * nw * 4, 256)) : nullptr;
     const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
     hipLaunchKernelGGL(conv3x3_wgrad_bf16_kernel, grid, dim3(kNW * 64), 2 * kBuf, stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
-    wgrad_launch_reduce(a.part, dw, nw, a.splits, stream);
-    if (db) wgrad_launch_reduce(a.dbpart, db, (size_t)Cout, a.splits, stream);
+    wgrad_launch_reduce(a.part, dw, nw, np, stream);
+    if (db) wgrad_launch_reduce(a.dbpart, db, (size_t)Cout, np, stream);
     return launch_status();
 }
 
