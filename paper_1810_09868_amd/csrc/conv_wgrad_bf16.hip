@@ -256,7 +256,10 @@ void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
     a.tiles_co = (Cout + kCO - 1) / kCO;
     a.tiles_ci = (CinP + kCI - 1) / kCI;
     const int groups = a.tiles_co * a.tiles_ci;
-    int splits = (1024 + groups - 1) / groups;   // two resident workgroups per CU, two rounds
+    // One round of two resident workgroups per CU.  Every workgroup writes 9 x 64 x 64 partial sums that the
+    // reduction reads back, 75 MB each way for 512 workgroups whatever the layer: a second round of
+    // workgroups (for balance) doubled that and measured 11 % slower over the whole stack.
+    int splits = (512 + groups - 1) / groups;
     if (splits > a.ntiles) splits = a.ntiles;
     if (splits < 1) splits = 1;
     a.tiles_per_split = (a.ntiles + splits - 1) / splits;
