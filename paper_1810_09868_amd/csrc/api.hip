@@ -39,10 +39,10 @@ int fc_forward(int dtype, int N, int In, int Out, const void *a, const void *w, 
                int relu, void *ws, hipStream_t s);
 size_t fc_bwd_workspace(int N, int In, int Out);
 int fc_backward(int N, int In, int Out, const float *a, const float *w, const float *dz, float *dw, float *db, float *da,
-                int relu_mask, void *ws, hipStream_t s, float *theta = nullptr, float lr = 0.f);
+                int relu_mask, void *ws, hipStream_t s);
 size_t fc_bwd_bf16_workspace(int N, int In, int Out);
 int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, const float *dz, float *dw, float *db, float *da,
-                     int relu_mask, void *ws, hipStream_t s, float *theta = nullptr, bf16_t *copy = nullptr, float lr = 0.f);
+                     int relu_mask, void *ws, hipStream_t s);
 
 namespace {
 
@@ -289,21 +289,16 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
     const char *fc_in[3] = {ws + L.pooled[15], ws + L.z1, ws + L.z2};
     float *fc_dz[3] = {F(ws + L.dz1), F(ws + L.dz2), F(ws + L.dlogits)};
     float *dflat = F(mixed ? ws + L.dflat32 : ws + L.gA);
-    // When the caller does not ask for the gradients, the dense layers' weights (86 % of the parameters) take
-    // their step inside the weight-gradient kernels: the gradient is then neither written nor read back.
-    const bool fused_fc = grads_out == nullptr;
     for (int l = 2; l >= 0; --l) {
         float *da = l == 0 ? dflat : fc_dz[l - 1];
         if (!rec.skip(K_FCDW)) {
             if (mixed)
                 rec.rc = fc_backward_bf16(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const bf16_t *>(fc_in[l]),
                                           reinterpret_cast<const bf16_t *>(pk + P.fc_w[l]), fc_dz[l], F(gr + Pm.fc_w[l]),
-                                          F(gr + Pm.fc_b[l]), da, 1, ws + L.fcbws, s, fused_fc ? F(pm + Pm.fc_w[l]) : nullptr,
-                                          reinterpret_cast<bf16_t *>(pk + P.fc_w[l]), c->lr);
+                                          F(gr + Pm.fc_b[l]), da, 1, ws + L.fcbws, s);
             else
                 rec.rc = fc_backward(N, P.fc_in[l], P.fc_out[l], reinterpret_cast<const float *>(fc_in[l]), F(pk + P.fc_w[l]),
-                                     fc_dz[l], F(gr + P.fc_w[l]), F(gr + P.fc_b[l]), da, 1, ws + L.fcbws, s,
-                                     fused_fc ? F(pk + P.fc_w[l]) : nullptr, c->lr);
+                                     fc_dz[l], F(gr + P.fc_w[l]), F(gr + P.fc_b[l]), da, 1, ws + L.fcbws, s);
         }
         rec.skip(K_FCDA);  // issued by the same call; listed for the plan
     }
@@ -348,12 +343,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_F32, P.fc_out[l], gr + Pm.fc_b[l], grads_out->fc_b[l], s));
     }
     if (!mixed) {
-        if (fused_fc) {   // everything but the dense weights, which lie between the convolution biases and the dense biases
-            VGG_STEP(rec, K_OTHER, sgd_update(P.fc_w[0] / 4, F(pk), F(gr), c->lr, s));
-            VGG_STEP(rec, K_OTHER, sgd_update((P.total - P.fc_b[0]) / 4, F(pk + P.fc_b[0]), F(gr + P.fc_b[0]), c->lr, s));
-        } else {
-            VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
-        }
+        VGG_STEP(rec, K_OTHER, sgd_update(P.total / 4, F(pk), F(gr), c->lr, s));
         return;
     }
     // master <- master - lr * gradient, working copy <- master (bf16 weights, fp32 biases).  Inside the two
@@ -377,7 +367,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         for (int l = 0; l < VGG19_NUM_CONV; ++l)
             VGG_STEP(rec, K_OTHER, sgd_update_master(kConvCh[l][1], F(pm + Pm.conv_b[l]), F(gr + Pm.conv_b[l]), c->lr,
                                                      pk + P.conv_b[l], VGG_F32, s));
-    if (!fused_fc && !(fc_prop && group(Pm.fc_w[0], Pm.fc_b[0], P.fc_w[0], P.fc_b[0], VGG_BF16)))
+    if (!(fc_prop && group(Pm.fc_w[0], Pm.fc_b[0], P.fc_w[0], P.fc_b[0], VGG_BF16)))
         for (int l = 0; l < VGG19_NUM_FC; ++l)
             VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)P.fc_in[l] * P.fc_out[l], F(pm + Pm.fc_w[l]), F(gr + Pm.fc_w[l]),
                                                      c->lr, pk + P.fc_w[l], VGG_BF16, s));

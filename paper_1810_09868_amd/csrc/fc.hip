@@ -210,10 +210,8 @@ int fc_forward(int dtype, int N, int In, int Out, const void *a_, const void *w,
 // fp32.  Workgroup: 128 (o) x 128 (i) block of dW; the batch is the
 // contraction index, staged through LDS 32 rows at a time.  Wave (wo, wi)
 // owns a 64x64 sub-block = 2x2 MFMA tiles.
-// With theta, the epilogue takes the gradient step itself -- theta <- theta - lr * dW -- and dW is
-// not written.
 __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a, const float *__restrict__ dz,
-                                                    float *__restrict__ dw, int N, int In, int Out, float *theta, float lr)
+                                                    float *__restrict__ dw, int N, int In, int Out)
 {
     constexpr int ROW = 128 * 4 + 16;
     __shared__ __align__(16) char Ds[32 * ROW];
@@ -281,20 +279,6 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
 #pragma unroll
         for (int y = 0; y < 2; ++y) {
             const int i = i0 + wi * 64 + y * 32 + r;
-            if (theta) {
-                float t[16];   // all sixteen values requested before the first is stored
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                    t[e] = (o < Out && i < In) ? theta[(size_t)o * In + i] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                    if (o < Out && i < In) theta[(size_t)o * In + i] = sgd_step(t[e], acc[x][y][e], lr);
-                }
-                continue;
-            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
@@ -452,13 +436,11 @@ size_t fc_bwd_workspace(int N, int In, int Out)
     return round_up((size_t)fc_da_splits(a) * N * In * 4, 256);
 }
 
-// theta (optional): the weights take the step theta <- theta - lr * dW inside the weight-gradient kernel and dw
-// is not written; the data gradient, which reads the weights, is launched before it.
 int fc_backward(int N, int In, int Out, const float *a, const float *w, const float *dz, float *dw, float *db, float *da,
-                int relu_mask, void *ws, hipStream_t s, float *theta, float lr)
+                int relu_mask, void *ws, hipStream_t s)
 {
     const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
-    if (!theta) hipLaunchKernelGGL(fc_dw_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out, theta, lr);
+    hipLaunchKernelGGL(fc_dw_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out);
     if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
     if (da) {
         FcDaArgs p;
@@ -470,7 +452,6 @@ int fc_backward(int N, int In, int Out, const float *a, const float *w, const fl
         hipLaunchKernelGGL(fc_da_finish_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.part, a, da, n,
                            splits, relu_mask);
     }
-    if (theta) hipLaunchKernelGGL(fc_dw_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out, theta, lr);
     return launch_status();
 }
 
@@ -513,11 +494,8 @@ constexpr int kDwRows = 64;   // batch rows per pass of the dW kernel: four MFMA
 
 // dW = dz^T * a.  Workgroup: 128 (o) x 128 (i) block of dW; wave (wo, wi) owns a 64 x 64 sub-block = 2 x 2 MFMA
 // tiles.  dzb: dz rounded to bf16, rows of OutP >= Out + 7 elements (a multiple of 8), zeros beyond Out.
-// With theta (the fp32 master weights), the epilogue takes the gradient step itself and refreshes the bf16 working
-// copy; dW is then not written.
 __global__ __launch_bounds__(256) void fc_dw_bf16_kernel(const bf16_t *__restrict__ a, const bf16_t *__restrict__ dzb,
-                                                            float *__restrict__ dw, int N, int In, int Out, int OutP,
-                                                            float *theta, bf16_t *copy, float lr)
+                                                            float *__restrict__ dw, int N, int In, int Out, int OutP)
 {
     __shared__ __align__(16) char Ds[kDwRows * kTrRow];
     __shared__ __align__(16) char As[kDwRows * kTrRow];
@@ -577,24 +555,6 @@ __global__ __launch_bounds__(256) void fc_dw_bf16_kernel(const bf16_t *__restric
 #pragma unroll
         for (int y = 0; y < 2; ++y) {
             const int i = i0 + wi * 64 + y * 32 + r;
-            if (theta) {
-                float t[16];   // all sixteen values requested before the first is stored
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                    t[e] = (o < Out && i < In) ? theta[(size_t)o * In + i] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                    if (o < Out && i < In) {
-                        const float v = sgd_step(t[e], acc[x][y][e], lr);
-                        theta[(size_t)o * In + i] = v;
-                        copy[(size_t)o * In + i] = f32_to_bf16(v);
-                    }
-                }
-                continue;
-            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
@@ -736,11 +696,8 @@ size_t fc_bwd_bf16_workspace(int N, int In, int Out)
 
 // a [N][In] bf16, w [Out][In] bf16, dz [N][Out] fp32 -> dw [Out][In] fp32, db [Out] fp32 (may be null),
 // da [N][In] fp32 (may be null; optionally masked by a > 0).  In must be a multiple of 8.
-// theta, copy (optional, together): the fp32 master weights take the step theta <- theta - lr * dW inside the
-// weight-gradient kernel, which also rewrites their bf16 working copy (w); dw is then not written, and the data
-// gradient, which reads w, is launched before it.
 int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, const float *dz, float *dw, float *db, float *da,
-                     int relu_mask, void *ws, hipStream_t s, float *theta, bf16_t *copy, float lr)
+                     int relu_mask, void *ws, hipStream_t s)
 {
     FcDaBf16Args p;
     fc_da_bf16_plan(N, In, Out, p);
@@ -748,9 +705,7 @@ int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, c
     const size_t nd = (size_t)N * p.OutP;
     hipLaunchKernelGGL(fc_dz_to_bf16_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, dz, dzb, N, Out, p.OutP);
     const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
-    if (!theta)
-        hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dzb, dw, N, In, Out, p.OutP,
-                           theta, copy, lr);
+    hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dzb, dw, N, In, Out, p.OutP);
     if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
     if (da) {
         const int splits = fc_da_bf16_splits(p);
@@ -761,9 +716,6 @@ int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, c
         hipLaunchKernelGGL(fc_da_bf16_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.part, a, da, n,
                            splits, relu_mask);
     }
-    if (theta)
-        hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dzb, dw, N, In, Out, p.OutP,
-                           theta, copy, lr);
     return launch_status();
 }
 

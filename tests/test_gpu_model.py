@@ -494,10 +494,9 @@ def test_full_vgg19_train_step_batch100_is_mean_of_chunks(dtype):
 @pytest.mark.parametrize("size", ["tiny", "224"])
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 def test_train_step_without_gradient_output_leaves_the_same_parameters(dtype, size):
-    # A caller that does not ask for the gradients gets the dense layers' update inside their
-    # weight-gradient kernels (the gradient is never written); the parameters, master and working
-    # copy, must come out bit-identical to the path that writes the gradients and updates
-    # afterwards -- over two steps, so that the second runs on the first's updated weights.
+    # Asking for the gradients (which adds the conversions to the canonical layout) must not change
+    # the step: parameters, master and working copy, come out bit-identical either way -- over two
+    # steps, so that the second runs on the first's updated weights.
     if size == "tiny":
         inp, shape = synth.tiny_config(seed=9), (2, 32, 32, 512, 10)
     else:
