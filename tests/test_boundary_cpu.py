@@ -107,3 +107,13 @@ def test_launch_plan_matches_paper_op_counts():
     assert tr.count(2) == 15 and tr.count(3) == 16
     assert tr.count(5) == gold["select-and-scatter"][1] == 5
     assert tr.count(6) + tr.count(7) + tr.count(8) == gold["dot"][1] == 9
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: no collectives, no sharding; the benchmark says so instead of starting
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
