@@ -14,7 +14,10 @@ int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const v
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
 size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout);
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, hipStream_t stream);
+                       void *ws, hipStream_t stream, int x_channels = 0);
+// Channels per pixel of the NHWC copy of the images that the first layer's weight gradient reads: with bf16
+// operands one 16-byte segment (the three channels and five zeros) instead of a whole 64-byte row.
+inline int x0_channels(int dtype, int cinp0) { return dtype == VGG_BF16 ? 8 : cinp0; }
 int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
                   hipStream_t stream);
 size_t mfma_probe_sink_bytes();
@@ -123,7 +126,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
     const size_t es = dtype_size(c->dtype);
     const size_t N = c->N;
     int h = c->H, w = c->W;
-    L.x0 = b.take(N * h * w * P.cinp[0] * es);
+    L.x0 = b.take(N * h * w * x0_channels(c->dtype, P.cinp[0]) * es);
     size_t max_act = 0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         L.H[l] = h; L.W[l] = w;
@@ -227,7 +230,7 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
     const int dt = c->dtype, N = c->N;
     // The first convolution reads the NCHW batch itself; training also keeps a channel-padded NHWC copy
     // of the images, which the first layer's weight gradient reads.
-    if (training) VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, P.cinp[0], x, ws + L.x0, s));
+    if (training) VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, x0_channels(dt, P.cinp[0]), x, ws + L.x0, s));
     const char *cur = ws + L.x0;
     for (int l = 0; l < VGG19_NUM_CONV; ++l) {
         char *out = ws + L.act[l];
@@ -317,7 +320,8 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         if (mixed)
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad_bf16(N, H, W, P.cinp[l], Cout, reinterpret_cast<const bf16_t *>(xin),
                                                      reinterpret_cast<const bf16_t *>(gbuf[cur]), F(gr + Pm.conv_w[l]),
-                                                     F(gr + Pm.conv_b[l]), ws + L.wgws, s));
+                                                     F(gr + Pm.conv_b[l]), ws + L.wgws, s,
+                                                     l == 0 ? x0_channels(dt, P.cinp[0]) : 0));
         else
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin),
                                                 F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));

@@ -56,11 +56,11 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 __device__ const u32x4_t kZero16[1] = {};        // what a segment outside the tensors reads
 
 struct WgradBf16Args {
-    const bf16_t *x;  // [M][CinP]
+    const bf16_t *x;  // [M][XC]: the first XC <= CinP channels; the others are taken as zero
     const bf16_t *g;  // [M][Cout]
     float *part;      // [splits][9][Cout][CinP]
     float *dbpart;    // [splits][Cout] or null
-    int N, H, W, CinP, Cout;
+    int N, H, W, CinP, Cout, XC;
     int tiles_co, tiles_ci, splits, tiles_per_split, ntiles;
     int tiles_w, tiles_hw;
     int narrow;       // CinP <= 32: the waves of a tap group split the patch rows, not the channels
@@ -113,7 +113,7 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         if (isg) { cp_dy[k] = row / kTW; cp_dx[k] = row % kTW; }
         else { cp_dy[k] = row / kHW - 1; cp_dx[k] = row % kHW - 1; }
         const int col = (isg ? co0 : ci0) + seg * 8;
-        const bool ok = seg < 8 && (isg || row < kHaloRows) && col < (isg ? p.Cout : p.CinP);
+        const bool ok = seg < 8 && (isg || row < kHaloRows) && col < (isg ? p.Cout : p.XC);
         cp_col[k] = ok ? col : -1;
     }
     auto issue = [&](int tile, char *base) __attribute__((always_inline)) {
@@ -126,7 +126,7 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
             const int h = h0 + cp_dy[k], w = w0 + cp_dx[k];
             const bool ok = cp_col[k] >= 0 && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
             const size_t pix = (size_t)((n * p.H + h) * p.W + w);
-            const bf16_t *src = cp_g[k] ? p.g + pix * p.Cout + cp_col[k] : p.x + pix * p.CinP + cp_col[k];
+            const bf16_t *src = cp_g[k] ? p.g + pix * p.Cout + cp_col[k] : p.x + pix * p.XC + cp_col[k];
             if (!ok) src = reinterpret_cast<const bf16_t *>(kZero16);
             const unsigned d = __builtin_amdgcn_readfirstlane(
                 (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(base + (k * kNW + wv) * 1024));
@@ -280,15 +280,19 @@ size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 }
 
 // x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
-// Cout and CinP must be multiples of 8 (16-byte channel segments).
+// Cout and CinP must be multiples of 8 (16-byte channel segments).  x_channels (optional): x holds only that many
+// channels per pixel (a multiple of 8, at most CinP), the rest count as zero -- the first layer's three channels
+// need one 16-byte segment per pixel, not a whole 64-byte row.
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, hipStream_t stream)
+                       void *ws, hipStream_t stream, int x_channels)
 {
     if (Cout % 8 || CinP % 8) return VGG_ERR_UNSUPPORTED;
+    if (x_channels == 0) x_channels = CinP;
+    if (x_channels % 8 || x_channels > CinP) return VGG_ERR_UNSUPPORTED;
     if ((long long)N * H * W >= (1ll << 31) / 2) return VGG_ERR_UNSUPPORTED;
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
-    a.x = x; a.g = g;
+    a.x = x; a.g = g; a.XC = x_channels;
     const size_t nw = (size_t)9 * Cout * CinP;
     a.part = static_cast<float *>(ws);
     const int np = wgrad_bf16_partials(a);
