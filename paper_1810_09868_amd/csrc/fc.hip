@@ -287,14 +287,22 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
         }
 }
 
-// db[o] = sum_n dz[n][o]
-__global__ void fc_db_kernel(const float *__restrict__ dz, float *__restrict__ db, int N, int Out)
+// db[o] = sum_n dz[n][o].  A workgroup owns 64 outputs; each of its four waves sums every fourth row and
+// the four partial sums are added in a fixed order (one thread per output walking all rows alone was a
+// chain of N dependent loads on sixteen CUs: 29 us for 4096 outputs).
+__global__ __launch_bounds__(256) void fc_db_kernel(const float *__restrict__ dz, float *__restrict__ db, int N, int Out)
 {
-    const int o = blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= Out) return;
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int o = blockIdx.x * 64 + lane;
     float s = 0.f;
-    for (int n = 0; n < N; ++n) s += dz[(size_t)n * Out + o];
-    db[o] = s;
+    if (o < Out) {
+#pragma unroll 4
+        for (int n = wv; n < N; n += 4) s += dz[(size_t)n * Out + o];
+    }
+    part[wv][lane] = s;
+    __syncthreads();
+    if (wv == 0 && o < Out) db[o] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
 }
 
 // --------------------------------------------------- backward: da = dz * W
@@ -441,7 +449,7 @@ int fc_backward(int N, int In, int Out, const float *a, const float *w, const fl
 {
     const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
     hipLaunchKernelGGL(fc_dw_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dz, dw, N, In, Out);
-    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
+    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 63) / 64), dim3(256), 0, s, dz, db, N, Out);
     if (da) {
         FcDaArgs p;
         fc_da_plan(N, In, Out, p);
@@ -706,7 +714,7 @@ int fc_backward_bf16(int N, int In, int Out, const bf16_t *a, const bf16_t *w, c
     hipLaunchKernelGGL(fc_dz_to_bf16_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, dz, dzb, N, Out, p.OutP);
     const int tiles_i = (In + 127) / 128, tiles_o = (Out + 127) / 128;
     hipLaunchKernelGGL(fc_dw_bf16_kernel, dim3((unsigned)(tiles_i * tiles_o)), dim3(256), 0, s, a, dzb, dw, N, In, Out, p.OutP);
-    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 255) / 256), dim3(256), 0, s, dz, db, N, Out);
+    if (db) hipLaunchKernelGGL(fc_db_kernel, dim3((Out + 63) / 64), dim3(256), 0, s, dz, db, N, Out);
     if (da) {
         const int splits = fc_da_bf16_splits(p);
         p.dzb = dzb; p.w = w;
