@@ -118,7 +118,7 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
     return res
 
 
-def run_train_bench(N, steps, inp_seed=0, dtype_name="f32", extras=True):
+def run_train_bench(N, steps, inp_seed=0, dtype_name="f32", extras=True, graph=True):
     """Training step (forward, cross-entropy, backward, SGD) at the same shapes: extra context.  bf16: bf16
     operands, fp32 sums, fp32 master parameters."""
     import torch
@@ -138,15 +138,17 @@ def run_train_bench(N, steps, inp_seed=0, dtype_name="f32", extras=True):
         m.train_step(x, lab)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
-    # the same steps as one HIP graph: the training loop replayed by a single launch
-    g = m.capture_train_steps(x, lab, steps)
-    g.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g.replay()
-    torch.cuda.synchronize()
-    dt_graph = (time.perf_counter() - t0) / steps
-    del g
+    dt_graph = None
+    if graph:
+        # the same steps as one HIP graph: the training loop replayed by a single launch
+        g = m.capture_train_steps(x, lab, steps)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        dt_graph = (time.perf_counter() - t0) / steps
+        del g
     kinds, ms = B.vgg19_timed(m.cfg, True, x, lab, m.packed, m.logits, m.ws)
     names = {1: "conv_fwd", 2: "conv_dgrad", 3: "conv_wgrad", 4: "pool", 5: "pool_bwd", 6: "fc", 7: "fc_bwd", 9: "other"}
     by_kind = {}
@@ -163,7 +165,7 @@ def run_train_bench(N, steps, inp_seed=0, dtype_name="f32", extras=True):
                        ", batch %d, 3x224x224 (forward, mean cross-entropy, backward, SGD lr 0.01)" % N,
            "dtype": dtype_name, "ms_per_step": dt * 1e3, "images_per_s": N / dt, "tflops": flops / dt / 1e12,
            "pct_mfma_peak": 100.0 * flops / dt / 1e12 / PEAK_TFLOPS[dtype_name], "ms_by_kind": by_kind,
-           "as_one_graph": {"steps_per_graph": steps, "ms_per_step": dt_graph * 1e3}}
+           "as_one_graph": {"steps_per_graph": steps, "ms_per_step": dt_graph * 1e3} if graph else None}
     if extras:
         res["tiny_config_loop"] = tiny_loop_bench()
     return res
@@ -279,6 +281,9 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (convert_kernel<float,float>, 2^26 elements) "
                          "so that hardware byte counters can be scaled against a kernel of known traffic")
+    ap.add_argument("--train-only", action="store_true",
+                    help="profiling aid: time only the training step of --dtype (eager launches, no HIP graph) and "
+                         "print its record instead of the forward benchmark's line")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -296,6 +301,9 @@ def main():
         B.vgg_convert(B.F32, B.F32, 1 << 26, src, dst)
         torch.cuda.synchronize()
         del src, dst
+    if a.train_only:
+        print(json.dumps(run_train_bench(a.batch, a.steps, dtype_name=a.dtype, extras=False, graph=False)))
+        return
     inp = synth.full_config(a.batch, seed=0, with_labels=False)
     main_res = run_forward_bench(a.dtype, a.batch, a.steps, a.warmup, inp)
     out = {
