@@ -282,7 +282,8 @@ __global__ __launch_bounds__(256) void fc_dw_kernel(const float *__restrict__ a,
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                if (o < Out && i < In) dw[(size_t)o * In + i] = acc[x][y][e];
+                // (streamed out: 411 MB for the first dense layer, re-read only by the update, long after it has left every cache)
+                if (o < Out && i < In) __builtin_nontemporal_store(acc[x][y][e], &dw[(size_t)o * In + i]);
             }
         }
 }
@@ -566,7 +567,7 @@ __global__ __launch_bounds__(256) void fc_dw_bf16_kernel(const bf16_t *__restric
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int o = o0 + wo * 64 + x * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                if (o < Out && i < In) dw[(size_t)o * In + i] = acc[x][y][e];
+                if (o < Out && i < In) __builtin_nontemporal_store(acc[x][y][e], &dw[(size_t)o * In + i]);
             }
         }
 }
