@@ -2,6 +2,7 @@
 // launches; plus the two model-level launch sequences (section "VGG19 forward
 // pass" / "VGG19 backward pass").
 #include "common.h"
+#include "flip_jobs.h"
 
 namespace vgg {
 // kernels' host launchers (defined in the other translation units)
@@ -35,6 +36,7 @@ int pad_channels(int dtype, size_t pixels, int C, int Cpad, const void *x, void 
 int convert(int sd, int dd, size_t n, const void *src, void *dst, hipStream_t s);
 int pack_conv_w(int dtype, int Cin, int Cout, const float *w, void *dst, int flip, hipStream_t s, int colsP = 0);
 int flip_packed_w(int dst_dtype, int CinP, int Cout, int CoutP, const float *src, void *dst, hipStream_t s);
+int flip_packed_w_all(int dst_dtype, FlipJobs &jobs, hipStream_t s);
 int unpack_conv_w(int Cin, int Cout, const float *src, float *w, hipStream_t s, int CinP = 0);
 int permute_fc_cols(int dst_dtype, int Out, int C, int HW, int to_hwc, const float *src, void *dst, hipStream_t s);
 size_t fc_workspace(int dtype, int N, int In, int Out);
@@ -113,7 +115,8 @@ struct WsLayout {
     size_t z1, z2, logits, probs, fcws;
     size_t convpart;                   // partial sums of convolutions whose contraction is split
     // training only
-    size_t dlogits, dz2, dz1, gA, gB, wflip, grads, wgws, fcbws, rowloss;
+    size_t dlogits, dz2, dz1, gA, gB, grads, wgws, fcbws, rowloss;
+    size_t wflip[VGG19_NUM_CONV];      // data-gradient operands (flipped, transposed weights) of layers 1..15
     size_t dflat32;                    // bf16 training: fp32 gradient with respect to the flattened pool output
     size_t total;
     int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
@@ -177,14 +180,16 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         if (s > cpart) cpart = s;
     }
     L.convpart = b.take(cpart);
-    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.wflip = L.grads = L.wgws = L.fcbws = L.rowloss = L.dflat32 = 0;
+    for (int l = 0; l < VGG19_NUM_CONV; ++l) L.wflip[l] = 0;
+    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.grads = L.wgws = L.fcbws = L.rowloss = L.dflat32 = 0;
     if (training) {
         L.dlogits = b.take(N * c->classes * 4);
         L.dz2 = b.take(N * c->fc_hidden * 4);
         L.dz1 = b.take(N * c->fc_hidden * 4);
         L.gA = b.take(max_act);
         L.gB = b.take(max_act);
-        L.wflip = b.take((size_t)9 * 512 * 512 * es);
+        L.wflip[0] = 0;
+        for (int l = 1; l < VGG19_NUM_CONV; ++l) L.wflip[l] = b.take((size_t)9 * P.cinp[l] * kConvCh[l][1] * es);
         const bool mixed = c->dtype == VGG_BF16;
         L.grads = b.take(mixed ? packed_layout(c, true).total : P.total);
         if (mixed) L.dflat32 = b.take(N * P.fc_in[0] * 4);
@@ -306,7 +311,19 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         rec.skip(K_FCDA);  // issued by the same call; listed for the plan
     }
     if (mixed) VGG_STEP(rec, K_OTHER, convert(VGG_F32, VGG_BF16, (size_t)N * P.fc_in[0], dflat, ws + L.gA, s));
-    // convolution stack, last to first
+    // convolution stack, last to first.  The data gradients' operands first, all in one launch: the same
+    // implicit GEMM runs on flipped, transposed weights.
+    {
+        FlipJobs jobs;
+        jobs.n = 0;
+        for (int l = 1; l < VGG19_NUM_CONV; ++l) {
+            const int j = jobs.n++;
+            jobs.src[j] = F(pm + Pm.conv_w[l]);
+            jobs.dst[j] = ws + L.wflip[l];
+            jobs.CinP[j] = P.cinp[l]; jobs.Cout[j] = kConvCh[l][1]; jobs.CoutP[j] = kConvCh[l][1];
+        }
+        VGG_STEP(rec, K_OTHER, flip_packed_w_all(dt, jobs, s));
+    }
     char *gbuf[2] = {ws + L.gA, ws + L.gB};
     int cur = 0;  // gbuf[cur] holds the gradient w.r.t. the output of layer l (after its pool, if any)
     for (int l = VGG19_NUM_CONV - 1; l >= 0; --l) {
@@ -327,8 +344,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
                                                 F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
         if (l > 0) {
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
-            VGG_STEP(rec, K_OTHER, flip_packed_w(dt, P.cinp[l], Cout, Cout, F(pm + Pm.conv_w[l]), ws + L.wflip, s));
-            VGG_STEP(rec, K_DGRAD, conv3x3_igemm(dt, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip, nullptr, xin,
+            VGG_STEP(rec, K_DGRAD, conv3x3_igemm(dt, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip[l], nullptr, xin,
                                                 gbuf[cur ^ 1], nullptr, nullptr, 0, ws + L.convpart, s));
             cur ^= 1;
         }

@@ -440,23 +440,28 @@ __global__ __launch_bounds__(kWaves * 64, 4) void conv3x3_wgrad_thin_kernel(Wgra
 // out[i] = sum over the splits of part[k][i], in a fixed order.  A workgroup owns 256/RY outputs;
 // thread row y adds the splits k = y, y + RY, ... and the RY rows are then added through LDS, so
 // that launches with few outputs and many splits (bias gradients, thin layers) still fill the chip.
+// Two sets of partials with the same number of splits (the weights' and the bias') share a launch:
+// outputs [0, n) come from part, outputs [n, n + n2) from part2.
 template <int RY>
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *part, float *out, size_t n, int splits)
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *part, float *out, size_t n, const float *part2,
+                                                           float *out2, size_t n2, int splits)
 {
     constexpr int RX = 256 / RY;
     __shared__ float red[256];
     const int x = threadIdx.x % RX, y = threadIdx.x / RX;
-    const size_t i = (size_t)blockIdx.x * RX + x;
+    size_t i = (size_t)blockIdx.x * RX + x;
+    const bool live = i < n + n2;
+    if (i >= n) { i -= n; part = part2; out = out2; n = n2; }
     float s = 0.f;
-    if (i < n)
+    if (live)
         for (int k = y; k < splits; k += RY) s += part[(size_t)k * n + i];
     if (RY == 1) {
-        if (i < n) out[i] = s;
+        if (live) out[i] = s;
         return;
     }
     red[threadIdx.x] = s;
     __syncthreads();
-    if (y == 0 && i < n) {
+    if (y == 0 && live) {
         float t = 0.f;
 #pragma unroll
         for (int r = 0; r < RY; ++r) t += red[r * RX + x];
@@ -464,20 +469,26 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *part, fl
     }
 }
 
-static void launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream)
+static void launch_reduce(const float *part, float *out, size_t n, const float *part2, float *out2, size_t n2, int splits,
+                          hipStream_t stream)
 {
+    const size_t total = n + n2;
     if (splits >= 128)
-        hipLaunchKernelGGL(wgrad_reduce_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, part, out, n, splits);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<16>, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, stream, part, out, n, part2,
+                           out2, n2, splits);
     else if (splits >= 16)
-        hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, stream, part, out, n, splits);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream, part, out, n, part2,
+                           out2, n2, splits);
     else
-        hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, part, out, n, splits);
+        hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, part, out, n, part2,
+                           out2, n2, splits);
 }
 
-// (also used by the bf16 weight-gradient kernel)
-void wgrad_launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream)
+// (also used by the bf16 weight-gradient kernel; part2/out2 may be null with n2 = 0)
+void wgrad_launch_reduce(const float *part, float *out, size_t n, const float *part2, float *out2, size_t n2, int splits,
+                         hipStream_t stream)
 {
-    launch_reduce(part, out, n, splits, stream);
+    launch_reduce(part, out, n, part2, out2, n2, splits, stream);
 }
 
 // Patch width of the general kernel for an image size: 16 or 14 where the image width divides into
@@ -561,8 +572,7 @@ int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float 
     else
         hipLaunchKernelGGL(conv3x3_wgrad_kernel<0>, grid, dim3(kWaves * 64), lds, stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
-    launch_reduce(a.part, dw, nw, a.splits, stream);
-    if (db) launch_reduce(a.dbpart, db, (size_t)Cout, a.splits, stream);
+    launch_reduce(a.part, dw, nw, a.dbpart, db, db ? (size_t)Cout : 0, a.splits, stream);
     return launch_status();
 }
 

@@ -34,7 +34,8 @@
 
 namespace vgg {
 
-void wgrad_launch_reduce(const float *part, float *out, size_t n, int splits, hipStream_t stream);
+void wgrad_launch_reduce(const float *part, float *out, size_t n, const float *part2, float *out2, size_t n2, int splits,
+                         hipStream_t stream);
 
 namespace {
 
@@ -300,8 +301,7 @@ int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x,
     const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
     hipLaunchKernelGGL(conv3x3_wgrad_bf16_kernel, grid, dim3(kNW * 64), 2 * kBuf, stream, a);
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
-    wgrad_launch_reduce(a.part, dw, nw, np, stream);
-    if (db) wgrad_launch_reduce(a.dbpart, db, (size_t)Cout, np, stream);
+    wgrad_launch_reduce(a.part, dw, nw, a.dbpart, db, db ? (size_t)Cout : 0, np, stream);
     return launch_status();
 }
 

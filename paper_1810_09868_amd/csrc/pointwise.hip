@@ -3,6 +3,7 @@
 // All are plain coalesced streaming kernels; NHWC tensors are handled as
 // vectors of 4 (fp32) or 8 (bf16) channels, i.e. 16 bytes per lane.
 #include "common.h"
+#include "flip_jobs.h"
 
 namespace vgg {
 
@@ -372,6 +373,52 @@ int flip_packed_w(int dst_dtype, int CinP, int Cout, int CoutP, const float *src
         hipLaunchKernelGGL(flip_packed_w_kernel<bf16_t>, grid, dim3(256), 0, s, src, (bf16_t *)dst, CinP, Cout, CoutP);
     else
         hipLaunchKernelGGL(flip_packed_w_kernel<float>, grid, dim3(256), 0, s, src, (float *)dst, CinP, Cout, CoutP);
+    return launch_status();
+}
+
+// The same for several tensors in one launch (a training step flips fifteen of them, each a few
+// microseconds of work): workgroups [first[j], first[j+1]) serve tensor j.
+template <typename TD>
+__global__ __launch_bounds__(256) void flip_packed_w_all_kernel(FlipJobs J)
+{
+    __shared__ float tile[32][33];
+    int j = 0;
+    while (j + 1 < J.n && (int)blockIdx.x >= J.first[j + 1]) ++j;
+    const float *__restrict__ src = J.src[j];
+    TD *__restrict__ dst = static_cast<TD *>(J.dst[j]);
+    const int CinP = J.CinP[j], Cout = J.Cout[j], CoutP = J.CoutP[j];
+    const int nbx = (CinP + 31) / 32, nby = (CoutP + 31) / 32;
+    const int local = (int)blockIdx.x - J.first[j];
+    const int bx = local % nbx, by = (local / nbx) % nby, t = local / (nbx * nby);
+    const int ci0 = bx * 32, co0 = by * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int co = co0 + r, ci = ci0 + tx;
+        tile[r][tx] = (co < Cout && ci < CinP) ? src[((size_t)(8 - t) * Cout + co) * CinP + ci] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int ci = ci0 + r, co = co0 + tx;
+        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + ((size_t)t * CinP + ci) * CoutP + co, tile[tx][r]);
+    }
+}
+
+// jobs.first is filled here
+int flip_packed_w_all(int dst_dtype, FlipJobs &jobs, hipStream_t s)
+{
+    if (jobs.n < 1 || jobs.n > kMaxFlipJobs) return VGG_ERR_UNSUPPORTED;
+    int total = 0;
+    for (int j = 0; j < jobs.n; ++j) {
+        jobs.first[j] = total;
+        total += ((jobs.CinP[j] + 31) / 32) * ((jobs.CoutP[j] + 31) / 32) * 9;
+    }
+    jobs.first[jobs.n] = total;
+    if (dst_dtype == VGG_BF16)
+        hipLaunchKernelGGL(flip_packed_w_all_kernel<bf16_t>, dim3((unsigned)total), dim3(256), 0, s, jobs);
+    else
+        hipLaunchKernelGGL(flip_packed_w_all_kernel<float>, dim3((unsigned)total), dim3(256), 0, s, jobs);
     return launch_status();
 }
 
