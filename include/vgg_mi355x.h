@@ -201,9 +201,13 @@ int vgg_maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy_nhw
 
 /* z[n,o] = f(bias[o] + sum_i w[o,i] * a[n,i])  -- the paper's
  * dense(W, x, b) = W*x + b applied to each image (listing "dense"; HLO
- * "dot").  a [N][In] and w [Out][In] in `dtype`; z [N][Out] in z_dtype;
- * In must be a multiple of 32.  The contraction is split over workgroups;
- * partial sums go to ws and are added in a fixed order. */
+ * "dot").  a [N][In] and w [Out][In] in `dtype`, rows densely packed; z
+ * [N][Out] in z_dtype.  Any N, In, Out > 0 (the paper's own example is
+ * 10 x 10 times a 10-vector); row lengths that are whole 64-byte units (In a
+ * multiple of 16 for VGG_F32, 32 for VGG_BF16, as in the network) take the
+ * fast path, others are completed with zeros in registers.  The contraction
+ * is split over workgroups; partial sums go to ws and are added in a fixed
+ * order. */
 size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias,
            void *z, int z_dtype, int relu, void *ws, size_t ws_bytes, void *stream);
@@ -212,7 +216,9 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
  * da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by (a[n,i] > 0)
  * when relu_mask != 0 (ReLU backward of the producer of a).  a and w are in
  * `dtype`; dz, dw, db and da are always fp32.  VGG_BF16: dz is rounded to
- * bf16 where it enters a product (not for db), sums are fp32.  The workspace
+ * bf16 where it enters a product (not for db), sums are fp32.  Any N, In, Out
+ * > 0 for VGG_F32; VGG_BF16 needs In to be a multiple of 8
+ * (VGG_ERR_UNSUPPORTED otherwise).  The workspace
  * is needed when da is requested and, for VGG_BF16, always. */
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, const void *dz,
@@ -281,6 +287,30 @@ int vgg19_train_step(const vgg_config *cfg, const float *x_nchw, const int32_t *
  * 1 conv fwd, 2 conv data-grad, 3 conv weight-grad, 4 pool, 5 pool bwd,
  * 6 dense fwd, 7 dense bwd (dW), 8 dense bwd (dA), 9 other. */
 int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
+
+/* Launch plan of one convolution call, for inspection (which kernel a shape
+ * gets decides the order of its sums, hence which results are bit-identical):
+ * op selects vgg_conv3x3_fwd, vgg_conv3x3_fwd_pool, vgg_conv3x3_bwd_data or
+ * vgg_conv3x3_bwd_weight with the same dtype and sizes (first call of the
+ * network, vgg_conv3x3_fwd_first, excluded).  Writes VGG_PLAN_INFO_LEN ints to
+ * info_host (host memory, cap >= VGG_PLAN_INFO_LEN else VGG_ERR_SHAPE):
+ *   [0] kernel: 0 register-staged implicit GEMM, 1 / 2 / 3 direct-to-LDS
+ *       implicit GEMM with room for 384 / 448 / 192 halo rows; weight
+ *       gradient: 100 linear tiles, 114 / 116 patches 14 / 16 pixels wide,
+ *       103 the kernel for at most three input channels (fp32); 116 / 117
+ *       the bf16 kernel and its variant for at most 32 input channels
+ *   [1] pixels per tile   [2] output channels per tile
+ *   [3] 0: a tile is consecutive pixels, 1: a patch of one image
+ *   [4] pixel tiles
+ *   [5] workgroups that share one tile's contraction (forward, data gradient)
+ *       or partial results that the fixed-order reduction adds (weight gradient)
+ *   [6] workgroups of the main launch */
+#define VGG_PLAN_FWD 0
+#define VGG_PLAN_FWD_POOL 1
+#define VGG_PLAN_BWD_DATA 2
+#define VGG_PLAN_BWD_WEIGHT 3
+#define VGG_PLAN_INFO_LEN 7
+int vgg_conv3x3_plan(int op, int dtype, int N, int H, int W, int Cin, int Cout, int *info_host, int cap);
 
 /* Profiling variant of the two model-level calls: runs one forward pass
  * (training == 0) or one training step (training != 0) with a HIP event

@@ -28,7 +28,7 @@ EXPORTS = [
     "vgg_softmax", "vgg_softmax_xent_bwd", "vgg_sgd_update",
     "vgg19_packed_bytes", "vgg19_forward_workspace_bytes", "vgg19_train_workspace_bytes",
     "vgg19_pack_params", "vgg19_unpack_params", "vgg19_forward", "vgg19_train_step", "vgg19_plan",
-    "vgg19_timed", "vgg_mfma_probe_sink_bytes", "vgg_mfma_probe",
+    "vgg19_timed", "vgg_mfma_probe_sink_bytes", "vgg_mfma_probe", "vgg_conv3x3_plan",
 ]
 
 
@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
         L.vgg19_plan.argtypes = [cfgp, _i, C.POINTER(C.c_int), _i]
         L.vgg19_timed.argtypes = [cfgp, _i, _vp, _vp, _vp, _sz, _vp, _vp, _sz, C.POINTER(C.c_int),
                                   C.POINTER(C.c_float), _i, _vp]
+        L.vgg_conv3x3_plan.argtypes = [_i] * 7 + [C.POINTER(C.c_int), _i]
         L.vgg_mfma_probe_sink_bytes.restype = _sz
         L.vgg_mfma_probe_sink_bytes.argtypes = []
         L.vgg_mfma_probe.argtypes = [_i, _i, _i, _vp, _sz, C.POINTER(C.c_double), _vp]
@@ -288,6 +289,16 @@ def vgg19_plan(cfg, training: bool) -> List[int]:
     buf = (C.c_int * n)()
     lib().vgg19_plan(C.byref(cfg), int(training), buf, n)
     return list(buf)
+
+
+PLAN_FWD, PLAN_FWD_POOL, PLAN_BWD_DATA, PLAN_BWD_WEIGHT = 0, 1, 2, 3
+
+
+def vgg_conv3x3_plan(op: int, dtype: int, N: int, H: int, W: int, Cin: int, Cout: int) -> List[int]:
+    """Launch plan of one convolution call (see the header): kernel, tile, splits, workgroups."""
+    info = (C.c_int * 7)()
+    _chk(lib().vgg_conv3x3_plan(op, dtype, N, H, W, Cin, Cout, info, 7), "vgg_conv3x3_plan")
+    return list(info)
 
 
 def vgg19_timed(cfg, training: bool, x_nchw, labels, packed, logits, ws):

@@ -4,6 +4,7 @@
 #include "common.h"
 #include "flip_jobs.h"
 
+
 namespace vgg {
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
@@ -12,15 +13,18 @@ size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cou
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
-size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout);
+void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout, bool pool, int info[7]);
+size_t conv3x3_wgrad_workspace(int N, int H, int W, int Cin, int CinP, int Cout);
+void conv3x3_wgrad_plan_info(int N, int H, int W, int Cin, int CinP, int Cout, int info[5]);
 size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout);
+void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5]);
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, hipStream_t stream, int x_channels = 0);
+                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels = 0);
 // Channels per pixel of the NHWC copy of the images that the first layer's weight gradient reads: with bf16
 // operands one 16-byte segment (the three channels and five zeros) instead of a whole 64-byte row.
 inline int x0_channels(int dtype, int cinp0) { return dtype == VGG_BF16 ? 8 : cinp0; }
 int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw, float *db, void *ws,
-                  hipStream_t stream);
+                  size_t ws_bytes, hipStream_t stream);
 size_t mfma_probe_sink_bytes();
 int mfma_probe(int dtype, int random, int iters, float *sink, double *flops, hipStream_t stream);
 int maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *arg, hipStream_t s);
@@ -118,6 +122,7 @@ struct WsLayout {
     size_t dlogits, dz2, dz1, gA, gB, grads, wgws, fcbws, rowloss;
     size_t wflip[VGG19_NUM_CONV];      // data-gradient operands (flipped, transposed weights) of layers 1..15
     size_t dflat32;                    // bf16 training: fp32 gradient with respect to the flattened pool output
+    size_t wgws_bytes;                 // size of the weight gradients' partial-sum buffer at wgws
     size_t total;
     int H[VGG19_NUM_CONV], W[VGG19_NUM_CONV];  // spatial size of each conv layer
 };
@@ -181,7 +186,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
     }
     L.convpart = b.take(cpart);
     for (int l = 0; l < VGG19_NUM_CONV; ++l) L.wflip[l] = 0;
-    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.grads = L.wgws = L.fcbws = L.rowloss = L.dflat32 = 0;
+    L.dlogits = L.dz2 = L.dz1 = L.gA = L.gB = L.grads = L.wgws = L.fcbws = L.rowloss = L.dflat32 = L.wgws_bytes = 0;
     if (training) {
         L.dlogits = b.take(N * c->classes * 4);
         L.dz2 = b.take(N * c->fc_hidden * 4);
@@ -196,7 +201,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
         size_t wg = 0, fb = 0;
         for (int l = 0; l < VGG19_NUM_CONV; ++l) {
             const size_t s = mixed ? conv3x3_wgrad_bf16_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1])
-                                   : conv3x3_wgrad_workspace(c->N, L.H[l], L.W[l], P.cinp[l], kConvCh[l][1]);
+                                   : conv3x3_wgrad_workspace(c->N, L.H[l], L.W[l], kConvCh[l][0], P.cinp[l], kConvCh[l][1]);
             if (s > wg) wg = s;
         }
         for (int l = 0; l < VGG19_NUM_FC; ++l) {
@@ -204,6 +209,7 @@ WsLayout ws_layout(const vgg_config *c, const PackedLayout &P, bool training)
             if (s > fb) fb = s;
         }
         L.wgws = b.take(wg);
+        L.wgws_bytes = wg;
         L.fcbws = b.take(fb);
         L.rowloss = b.take(N * 4);
     }
@@ -337,11 +343,12 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         if (mixed)
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad_bf16(N, H, W, P.cinp[l], Cout, reinterpret_cast<const bf16_t *>(xin),
                                                      reinterpret_cast<const bf16_t *>(gbuf[cur]), F(gr + Pm.conv_w[l]),
-                                                     F(gr + Pm.conv_b[l]), ws + L.wgws, s,
+                                                     F(gr + Pm.conv_b[l]), ws + L.wgws, L.wgws_bytes, s,
                                                      l == 0 ? x0_channels(dt, P.cinp[0]) : 0));
         else
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin),
-                                                F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws, s));
+                                                F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws,
+                                                L.wgws_bytes, s));
         if (l > 0) {
             // data gradient = the same implicit GEMM with flipped, transposed weights; fused ReLU mask (x > 0)
             VGG_STEP(rec, K_DGRAD, conv3x3_igemm(dt, N, H, W, Cout, Cin, gbuf[cur], ws + L.wflip[l], nullptr, xin,
@@ -586,7 +593,7 @@ size_t vgg_conv3x3_bwd_weight_workspace_bytes(int dtype, int N, int H, int W, in
     if (!dtype_ok(dtype) || !conv_shape_ok(N, H, W, Cin, Cout)) return 0;
     const int cp = padded_channels(dtype, Cin);
     size_t pad = cp == Cin ? 0 : round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
-    return pad + (dtype == VGG_F32 ? conv3x3_wgrad_workspace(N, H, W, cp, Cout) : conv3x3_wgrad_bf16_workspace(N, H, W, cp, Cout));
+    return pad + (dtype == VGG_F32 ? conv3x3_wgrad_workspace(N, H, W, Cin, cp, Cout) : conv3x3_wgrad_bf16_workspace(N, H, W, cp, Cout));
 }
 
 int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, const void *x, const void *g, float *dw,
@@ -606,11 +613,16 @@ int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, co
         const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, wsp, s);
         if (rc) return rc;
         x = wsp;
-        wsp += round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+        const size_t pad = round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+        wsp += pad;
+        ws_bytes -= pad;
     }
+    // (the launchers compare what is left of the workspace with the partial sums of the plan they run)
     if (dtype == VGG_BF16)
-        return conv3x3_wgrad_bf16(N, H, W, cp, Cout, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), dw, db, wsp, s);
-    return conv3x3_wgrad(N, H, W, Cin, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp, s);
+        return conv3x3_wgrad_bf16(N, H, W, cp, Cout, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), dw, db, wsp,
+                                  ws_bytes, s);
+    return conv3x3_wgrad(N, H, W, Cin, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp,
+                         ws_bytes, s);
 }
 
 int vgg_maxpool2x2(int dtype, int N, int H, int W, int C, const void *x, void *y, uint8_t *argmax, void *stream)
@@ -633,7 +645,7 @@ int vgg_maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy, co
 
 size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out)
 {
-    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
+    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0) return 0;
     return fc_workspace(dtype, N, In, Out);
 }
 
@@ -642,7 +654,7 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
 {
     if (!a || !w || !z) return VGG_ERR_NULL;
     if (!dtype_ok(dtype) || !dtype_ok(z_dtype)) return VGG_ERR_DTYPE;
-    if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
+    if (N <= 0 || In <= 0 || Out <= 0) return VGG_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(w) || !aligned16(z) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
     if (!ws || ws_bytes < fc_workspace(dtype, N, In, Out)) return VGG_ERR_WORKSPACE;
     return fc_forward(dtype, N, In, Out, a, w, bias, z, z_dtype, relu ? 1 : 0, ws, (hipStream_t)stream);
@@ -650,7 +662,7 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
 
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out)
 {
-    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0 || In % 32) return 0;
+    if (!dtype_ok(dtype) || N <= 0 || In <= 0 || Out <= 0 || (dtype == VGG_BF16 && In % 8)) return 0;
     return dtype == VGG_F32 ? fc_bwd_workspace(N, In, Out) : fc_bwd_bf16_workspace(N, In, Out);
 }
 
@@ -659,7 +671,8 @@ int vgg_fc_bwd(int dtype, int N, int In, int Out, const void *a, const void *w, 
 {
     if (!a || !w || !dz || !dw) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
-    if (N <= 0 || In <= 0 || Out <= 0 || In % 32) return VGG_ERR_SHAPE;
+    if (N <= 0 || In <= 0 || Out <= 0) return VGG_ERR_SHAPE;
+    if (dtype == VGG_BF16 && In % 8) return VGG_ERR_UNSUPPORTED;   // 16-byte segments of bf16 rows
     if (!aligned16(a) || !aligned16(w) || !aligned16(dz) || !aligned16(dw) || (da && !aligned16(da)) || (ws && !aligned16(ws)))
         return VGG_ERR_ALIGN;
     // (bf16: the rounded copy of dz lives in the workspace, so it is needed even without da)
@@ -860,6 +873,36 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap)
     else
         run_forward(cfg, P, L, nullptr, nullptr, nullptr, nullptr, true, nullptr, false, nullptr, rec);
     return rec.n;
+}
+
+int vgg_conv3x3_plan(int op, int dtype, int N, int H, int W, int Cin, int Cout, int *info_host, int cap)
+{
+    if (!info_host) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (!conv_shape_ok(N, H, W, Cin, Cout) || op < VGG_PLAN_FWD || op > VGG_PLAN_BWD_WEIGHT || cap < VGG_PLAN_INFO_LEN)
+        return VGG_ERR_SHAPE;
+    int info[VGG_PLAN_INFO_LEN] = {0, 0, 0, 0, 0, 1, 0};
+    if (op == VGG_PLAN_BWD_WEIGHT) {
+        int w[5];
+        const int cp = padded_channels(dtype, Cin);
+        if (dtype == VGG_F32) conv3x3_wgrad_plan_info(N, H, W, Cin, cp, Cout, w);
+        else conv3x3_wgrad_bf16_plan_info(N, H, W, cp, Cout, w);
+        info[0] = 100 + w[0];
+        info[1] = w[0] == 14 ? 56 : 64;
+        info[2] = 64;
+        info[3] = (w[0] == 0 || w[0] == 3) ? 0 : 1;
+        info[4] = w[1];
+        info[5] = w[2];
+        info[6] = w[4];
+    } else if (op == VGG_PLAN_FWD_POOL && !conv3x3_pool_fusable(dtype, H, W, Cout)) {
+        return VGG_ERR_UNSUPPORTED;
+    } else if (op == VGG_PLAN_BWD_DATA) {
+        conv3x3_igemm_plan_info(dtype, N, H, W, padded_channels(dtype, Cout), Cin, false, info);
+    } else {
+        conv3x3_igemm_plan_info(dtype, N, H, W, padded_channels(dtype, Cin), Cout, op == VGG_PLAN_FWD_POOL, info);
+    }
+    for (int i = 0; i < VGG_PLAN_INFO_LEN; ++i) info_host[i] = info[i];
+    return VGG_OK;
 }
 
 size_t vgg_mfma_probe_sink_bytes(void) { return mfma_probe_sink_bytes(); }

@@ -721,6 +721,22 @@ size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cou
     return c.ksplit > 1 ? round_up((size_t)c.ksplit * N * H * W * Cout * 4, 256) : 0;
 }
 
+// For inspection: {kernel (0 register-staged, 1 / 2 / 3 direct-to-LDS with 384 / 448 / 192 halo rows), pixels per
+// tile, channels per tile, tile mode (0 consecutive pixels, 1 patches), pixel tiles, workgroups per tile (split
+// contraction), workgroups}.
+void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout, bool pool, int info[7])
+{
+    const ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, pool);
+    const int bn = c.narrow ? 64 : 128;
+    info[0] = c.half ? 3 : (c.dma ? 1 : (c.dma_big ? 2 : 0));
+    info[1] = c.g.rows;
+    info[2] = bn;
+    info[3] = c.g.mode;
+    info[4] = c.g.ntiles;
+    info[5] = c.ksplit;
+    info[6] = c.g.ntiles * ((Cout + bn - 1) / bn) * c.ksplit;
+}
+
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout)
 {
     return H % 16 == 0 && W % kTileW == 0 && Cout % (16 / dtype_size(dtype)) == 0;

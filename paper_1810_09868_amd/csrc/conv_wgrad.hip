@@ -526,20 +526,45 @@ static void wgrad_plan(int N, int H, int W, int CinP, int Cout, WgradArgs &a, bo
     a.splits = (a.geo.ntiles + a.tiles_per_split - 1) / a.tiles_per_split;
 }
 
-size_t conv3x3_wgrad_workspace(int N, int H, int W, int CinP, int Cout)
+// The thin kernel serves layers with at most three input channels; it tiles the pixels linearly, so its
+// split count differs from the general kernel's.  Query and launch must agree on which one runs.
+static bool wgrad_is_thin(int Cin, int CinP) { return Cin <= 3 && CinP <= kBCI; }
+
+static size_t wgrad_ws_bytes(const WgradArgs &a)
+{
+    return round_up((size_t)a.splits * 9 * a.Cout * a.CinP * 4, 256) + round_up((size_t)a.splits * a.Cout * 4, 256);
+}
+
+size_t conv3x3_wgrad_workspace(int N, int H, int W, int Cin, int CinP, int Cout)
 {
     WgradArgs a;
-    wgrad_plan(N, H, W, CinP, Cout, a);
-    return round_up((size_t)a.splits * 9 * Cout * CinP * 4, 256) + round_up((size_t)a.splits * Cout * 4, 256);
+    wgrad_plan(N, H, W, CinP, Cout, a, wgrad_is_thin(Cin, CinP));
+    return wgrad_ws_bytes(a);
+}
+
+// For inspection: {kernel (0 linear tiles, 14 / 16 patch width, 3 thin), pixel tiles, splits, tiles per split,
+// workgroups}.
+void conv3x3_wgrad_plan_info(int N, int H, int W, int Cin, int CinP, int Cout, int info[5])
+{
+    WgradArgs a;
+    const bool thin = wgrad_is_thin(Cin, CinP);
+    wgrad_plan(N, H, W, CinP, Cout, a, thin);
+    info[0] = thin ? 3 : (a.geo.mode == 1 ? a.geo.TW : 0);
+    info[1] = a.geo.ntiles;
+    info[2] = a.splits;
+    info[3] = a.tiles_per_split;
+    info[4] = a.tiles_co * a.tiles_ci * a.splits;
 }
 
 // x [M][CinP] fp32 (channels >= Cin are zero), g [M][Cout] fp32 -> dw [9][Cout][CinP], db [Cout] (may be null).
+// ws_bytes: size of ws; the launch is refused when the partial sums of its own plan would not fit.
 int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float *x, const float *g, float *dw,
-                  float *db, void *ws, hipStream_t stream)
+                  float *db, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    const bool thin = Cin <= 3 && CinP <= kBCI;
+    const bool thin = wgrad_is_thin(Cin, CinP);
     WgradArgs a;
     wgrad_plan(N, H, W, CinP, Cout, a, thin);
+    if (ws_bytes < wgrad_ws_bytes(a)) return VGG_ERR_WORKSPACE;
     a.x = x; a.g = g;
     const size_t nw = (size_t)9 * Cout * CinP;
     a.part = static_cast<float *>(ws);

@@ -272,12 +272,30 @@ inline int wgrad_bf16_partials(const WgradBf16Args &a) { return a.narrow ? 2 * a
 
 }  // namespace
 
+static size_t wgrad_bf16_ws_bytes(const WgradBf16Args &a)
+{
+    const size_t np = (size_t)wgrad_bf16_partials(a);
+    return round_up(np * 9 * a.Cout * a.CinP * 4, 256) + round_up(np * a.Cout * 4, 256);
+}
+
 size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 {
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
-    const size_t np = (size_t)wgrad_bf16_partials(a);
-    return round_up(np * 9 * Cout * CinP * 4, 256) + round_up(np * Cout * 4, 256);
+    return wgrad_bf16_ws_bytes(a);
+}
+
+// For inspection: {kernel (16: 4 x 16 patches; 17: the same with both waves of a tap group on one channel
+// half), pixel tiles, partial results, tiles per split, workgroups}.
+void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5])
+{
+    WgradBf16Args a;
+    wgrad_bf16_plan(N, H, W, CinP, Cout, a);
+    info[0] = a.narrow ? 17 : 16;
+    info[1] = a.ntiles;
+    info[2] = wgrad_bf16_partials(a);
+    info[3] = a.tiles_per_split;
+    info[4] = a.tiles_co * a.tiles_ci * a.splits;
 }
 
 // x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
@@ -285,7 +303,7 @@ size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 // channels per pixel (a multiple of 8, at most CinP), the rest count as zero -- the first layer's three channels
 // need one 16-byte segment per pixel, not a whole 64-byte row.
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, hipStream_t stream, int x_channels)
+                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels)
 {
     if (Cout % 8 || CinP % 8) return VGG_ERR_UNSUPPORTED;
     if (x_channels == 0) x_channels = CinP;
@@ -293,6 +311,7 @@ int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x,
     if ((long long)N * H * W >= (1ll << 31) / 2) return VGG_ERR_UNSUPPORTED;
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
+    if (ws_bytes < wgrad_bf16_ws_bytes(a)) return VGG_ERR_WORKSPACE;
     a.x = x; a.g = g; a.XC = x_channels;
     const size_t nw = (size_t)9 * Cout * CinP;
     a.part = static_cast<float *>(ws);

@@ -50,13 +50,34 @@ struct FcArgs {
     const char *w;   // [Out][In]
     float *part;     // [splits][N][Out]
     int N, In, Out;
-    int units;            // In * sizeof(T) / 64
+    int units;            // 64-byte K units per row: In * sizeof(T) / 64, rounded up
     int units_per_split;
     int tiles_n;          // column tiles
     int tiles_m;          // row tiles
 };
 
+// 16 bytes at byte offset `off` of a row of `rowbytes` bytes, zeros at and beyond the row's end.
+// vec: rows are 16-byte aligned and a whole number of 16-byte segments (one load); otherwise the
+// segment is gathered element by element, so that any row length works.
 template <typename T>
+__device__ __forceinline__ uint4 load_seg(const char *row, size_t off, size_t rowbytes, bool vec)
+{
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (vec) {
+        if (off < rowbytes) v = *reinterpret_cast<const uint4 *>(row + off);
+        return v;
+    }
+    T e[16 / sizeof(T)];
+#pragma unroll
+    for (int k = 0; k < (int)(16 / sizeof(T)); ++k)
+        e[k] = off + k * sizeof(T) < rowbytes ? reinterpret_cast<const T *>(row + off)[k] : (T)0;
+    __builtin_memcpy(&v, e, 16);
+    return v;
+}
+
+// EXACT: every row is a whole number of 64-byte units (In a multiple of 16 fp32 / 32 bf16), the case
+// of the network's own layers.  Otherwise the last unit of a row is completed with zeros in registers.
+template <typename T, bool EXACT>
 __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
 {
     __shared__ __align__(16) char As[4 * 128 * kFcRow];  // [unit][row][80]
@@ -70,6 +91,7 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
     const int u_begin = split * p.units_per_split;
     const int u_end = min(u_begin + p.units_per_split, p.units);
     const size_t rowbytes = (size_t)p.In * sizeof(T);
+    const bool vec = EXACT || rowbytes % 16 == 0;
 
     const int ocol = o0 + wv * 32 + r;
     const bool ook = ocol < p.Out;
@@ -93,8 +115,10 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 bf[u][g] = make_uint4(0, 0, 0, 0);
-                if (u < nu && ook)
-                    bf[u][g] = *reinterpret_cast<const uint4 *>(wrow + (size_t)(u0 + u) * 64 + g * 32);
+                if (u < nu && ook) {
+                    if (EXACT) bf[u][g] = *reinterpret_cast<const uint4 *>(wrow + (size_t)(u0 + u) * 64 + g * 32);
+                    else bf[u][g] = load_seg<T>(wrow - khalf * 16, (size_t)(u0 + u) * 64 + g * 32 + khalf * 16, rowbytes, vec);
+                }
             }
     };
     auto load_a = [&](int u0, uint4 (&av)[NA]) __attribute__((always_inline)) {
@@ -104,8 +128,10 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(FcArgs p)
             const int idx = tid + k * 256;
             const int seg = idx & 3, row = (idx >> 2) & 127, u = idx >> 9;
             av[k] = make_uint4(0, 0, 0, 0);
-            if (u < nu && row0 + row < p.N)
-                av[k] = *reinterpret_cast<const uint4 *>(p.a + (size_t)(row0 + row) * rowbytes + (size_t)(u0 + u) * 64 + seg * 16);
+            if (u < nu && row0 + row < p.N) {
+                if (EXACT) av[k] = *reinterpret_cast<const uint4 *>(p.a + (size_t)(row0 + row) * rowbytes + (size_t)(u0 + u) * 64 + seg * 16);
+                else av[k] = load_seg<T>(p.a + (size_t)(row0 + row) * rowbytes, (size_t)(u0 + u) * 64 + seg * 16, rowbytes, vec);
+            }
         }
     };
     uint4 bf_next[4][2], a_next[NA];
@@ -162,7 +188,7 @@ __global__ void fc_finish_kernel(const float *__restrict__ part, const float *__
 static void fc_plan(int dtype, int N, int In, int Out, FcArgs &a)
 {
     a.N = N; a.In = In; a.Out = Out;
-    a.units = In * dtype_size(dtype) / 64;
+    a.units = (In * dtype_size(dtype) + 63) / 64;
     a.tiles_n = (Out + 127) / 128;
     a.tiles_m = (N + 127) / 128;
     const int tiles = a.tiles_n * a.tiles_m;
@@ -192,10 +218,14 @@ int fc_forward(int dtype, int N, int In, int Out, const void *a_, const void *w,
     a.w = static_cast<const char *>(w);
     a.part = static_cast<float *>(ws);
     const dim3 grid((unsigned)(a.tiles_n * a.tiles_m * splits));
-    if (dtype == VGG_BF16)
-        hipLaunchKernelGGL(fc_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, a);
-    else
-        hipLaunchKernelGGL(fc_fwd_kernel<float>, grid, dim3(256), 0, s, a);
+    const bool exact = (size_t)In * dtype_size(dtype) % 64 == 0;
+    if (dtype == VGG_BF16) {
+        if (exact) hipLaunchKernelGGL((fc_fwd_kernel<bf16_t, true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((fc_fwd_kernel<bf16_t, false>), grid, dim3(256), 0, s, a);
+    } else {
+        if (exact) hipLaunchKernelGGL((fc_fwd_kernel<float, true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((fc_fwd_kernel<float, false>), grid, dim3(256), 0, s, a);
+    }
     if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
     const size_t n = (size_t)N * Out;
     const dim3 g2((unsigned)((n + 255) / 256));
@@ -321,6 +351,9 @@ struct FcDaArgs {
     int tiles_i, tiles_m, o_per_split;
 };
 
+// VEC: In is a multiple of 4, so a lane's four inputs are one aligned 16-byte load and store; otherwise
+// they are read and written one by one, with zeros beyond the row's end.
+template <bool VEC>
 __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
 {
     __shared__ __align__(16) char Ds[128 * kFcRow];  // dz rows, 16 outputs per chunk
@@ -333,7 +366,7 @@ __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
     const int split = b;
     const int row0 = tm * 128;
     const int icol = ti * 256 + wc * 128 + 4 * r;  // first of this lane's 4 inputs
-    const bool iok = icol < p.In;                  // In is a multiple of 4
+    const bool iok = icol < p.In;
     const int o_begin = split * p.o_per_split, o_end = min(o_begin + p.o_per_split, p.Out);
 
     f32x16 acc[2][4];
@@ -366,7 +399,13 @@ __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
                 // this lane's four contraction indices of half g: oc + 8g + 4*khalf + e
                 const int o = oc + g * 8 + khalf * 4 + e;
                 w_next[g][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (iok && o < o_end) w_next[g][e] = *reinterpret_cast<const f32x4 *>(p.w + (size_t)o * p.In + icol);
+                if (iok && o < o_end) {
+                    const float *wp = p.w + (size_t)o * p.In + icol;
+                    if (VEC) w_next[g][e] = *reinterpret_cast<const f32x4 *>(wp);
+                    else
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) w_next[g][e][j] = icol + j < p.In ? wp[j] : 0.f;
+                }
             }
     };
     if (o_begin < o_end) request(o_begin);
@@ -405,7 +444,12 @@ __global__ __launch_bounds__(256) void fc_da_kernel(FcDaArgs p)
                 const int row = row0 + wr * 64 + x * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
                 if (row < p.N) {
                     const f32x4 v = {acc[x][0][e], acc[x][1][e], acc[x][2][e], acc[x][3][e]};
-                    *reinterpret_cast<f32x4 *>(p.part + ((size_t)split * p.N + row) * p.In + icol) = v;
+                    float *dst = p.part + ((size_t)split * p.N + row) * p.In + icol;
+                    if (VEC) *reinterpret_cast<f32x4 *>(dst) = v;
+                    else
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (icol + j < p.In) dst[j] = v[j];
                 }
             }
     }
@@ -456,7 +500,8 @@ int fc_backward(int N, int In, int Out, const float *a, const float *w, const fl
         fc_da_plan(N, In, Out, p);
         const int splits = fc_da_splits(p);
         p.dz = dz; p.w = w; p.part = static_cast<float *>(ws);
-        hipLaunchKernelGGL(fc_da_kernel, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
+        if (In % 4 == 0) hipLaunchKernelGGL(fc_da_kernel<true>, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(fc_da_kernel<false>, dim3((unsigned)(p.tiles_i * p.tiles_m * splits)), dim3(256), 0, s, p);
         const size_t n = (size_t)N * In;
         hipLaunchKernelGGL(fc_da_finish_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.part, a, da, n,
                            splits, relu_mask);

@@ -53,7 +53,9 @@ def test_argument_validation_happens_on_the_host():
     assert L.vgg_conv3x3_bwd_weight(0, 1, 4, 4, 16, 16, a, a, a, None, None, 0, None) == -5
     assert L.vgg_maxpool2x2(0, 1, 5, 4, 8, a, a, None, None) == -2                        # odd H
     assert L.vgg_maxpool2x2(0, 1, 4, 4, 8, None, a, None, None) == -1
-    assert L.vgg_fc(0, 2, 48, 8, a, a, None, a, 0, 0, a, 1 << 30, None) == -2             # In % 32
+    assert L.vgg_fc(0, 2, 0, 8, a, a, None, a, 0, 0, a, 1 << 30, None) == -2
+    assert L.vgg_fc(0, 10, 10, 10, a, a, None, a, 0, 0, None, 0, None) == -5             # any In is a valid shape
+    assert L.vgg_fc_bwd(1, 2, 12, 8, a, a, a, a, None, None, 0, a, 1 << 30, None) == -7  # bf16 backward: In % 8
     assert L.vgg_fc(0, 2, 64, 8, a, a, None, a, 0, 0, None, 0, None) == -5
     assert L.vgg_softmax(0, 10, a, a, None) == -2
     assert L.vgg_sgd_update(0, a, a, 0.1, None) == -2
@@ -117,3 +119,61 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def _ru(v, a=256):
+    return (v + a - 1) // a * a
+
+
+def test_weight_gradient_workspace_query_covers_the_plan_that_runs():
+    # The partial sums of the weight gradient are [partials][9][Cout][CinP] and [partials][Cout]; the
+    # workspace query must be sized for the kernel that the launch picks for the same arguments (layers
+    # with at most three input channels take a kernel with its own pixel tiling and split count).
+    shapes = [(37, 55, 16, 3, 8), (57, 9, 42, 3, 64), (100, 224, 224, 3, 64), (2, 32, 32, 3, 64), (1, 7, 5, 1, 4),
+              (3, 20, 28, 2, 12), (5, 56, 56, 3, 32), (2, 14, 14, 512, 512), (3, 30, 18, 17, 24), (100, 14, 14, 512, 512),
+              (40, 28, 28, 256, 512), (9, 16, 48, 3, 16)]
+    for n in range(1, 60, 7):
+        for h in (3, 9, 16, 55):
+            for w in (5, 16, 42, 56):
+                shapes.append((n, h, w, 3, 8 * (1 + n % 5)))
+    for dtype in (B.F32, B.BF16):
+        for (n, h, w, ci, co) in shapes:
+            if dtype == B.BF16 and co % 8:
+                continue
+            info = B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, dtype, n, h, w, ci, co)
+            cp = B.vgg_padded_channels(dtype, ci)
+            partials = info[5]
+            assert partials >= 1 and info[6] >= 1
+            pad = 0 if cp == ci else _ru(n * h * w * cp * (4 if dtype == B.F32 else 2))
+            need = pad + _ru(partials * 9 * co * cp * 4) + _ru(partials * co * 4)
+            assert B.vgg_conv3x3_bwd_weight_workspace_bytes(dtype, n, h, w, ci, co) == need, (dtype, n, h, w, ci, co, info)
+            # one byte less is refused on the host, before anything is launched
+            a = 4096
+            assert B.lib().vgg_conv3x3_bwd_weight(dtype, n, h, w, ci, co, a, a, a, None, a, need - 1, None) == -5
+    # the kernel for thin layers is the one the plan names for the network's first layer
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 224, 224, 3, 64)[0] == 103
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 224, 224, 64, 64)[0] == 116
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 56, 56, 256, 256)[0] == 114
+
+
+def test_convolution_plan_query():
+    L = B.lib()
+    buf = (C.c_int * 7)()
+    assert L.vgg_conv3x3_plan(0, 0, 1, 4, 4, 16, 16, None, 7) == -1
+    assert L.vgg_conv3x3_plan(9, 0, 1, 4, 4, 16, 16, buf, 7) == -2
+    assert L.vgg_conv3x3_plan(0, 0, 1, 4, 4, 16, 16, buf, 3) == -2
+    assert L.vgg_conv3x3_plan(0, 4, 1, 4, 4, 16, 16, buf, 7) == -3
+    assert L.vgg_conv3x3_plan(B.PLAN_FWD_POOL, 0, 1, 14, 14, 16, 16, buf, 7) == -7     # pool fusion needs 16-pixel patches
+    # batch 100: 256-pixel tiles, contraction never split; the 14x14 layers take 64-wide column tiles (fp32: 128 pixels)
+    for dtype in (B.F32, B.BF16):
+        for (h, ci, co) in ((224, 64, 64), (112, 128, 128), (56, 256, 256), (28, 512, 512), (14, 512, 512)):
+            for op in (B.PLAN_FWD, B.PLAN_BWD_DATA):
+                info = B.vgg_conv3x3_plan(op, dtype, 100, h, h, ci, co)
+                assert info[5] == 1
+                assert info[1] == (128 if (dtype == B.F32 and h == 14) else 256)
+                assert info[2] == (64 if (co == 64 or h == 14) else 128)
+                assert info[1] * info[4] >= 100 * h * h
+    # a single image: the last stages split their contraction over several workgroups
+    assert B.vgg_conv3x3_plan(B.PLAN_FWD, B.BF16, 1, 14, 14, 512, 512)[5] > 1
+    assert B.vgg_conv3x3_fwd_workspace_bytes(B.BF16, 1, 14, 14, 512, 512) > 0
+    assert B.vgg_conv3x3_fwd_workspace_bytes(B.BF16, 100, 14, 14, 512, 512) == 0

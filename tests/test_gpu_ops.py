@@ -185,6 +185,49 @@ def _check_bwd_weight(dtype, shape, seed):
     assert torch.equal(dwp, dwp2)
 
 
+@pytest.mark.parametrize("shape", [(37, 55, 16, 3, 8), (57, 9, 42, 3, 64), (9, 16, 48, 2, 16), (2, 224, 224, 3, 64)])
+def test_conv3x3_bwd_weight_thin_layers_stay_inside_their_workspace(shape):
+    # At most three input channels: fp32 takes a kernel with its own pixel tiling, hence its own number of
+    # partial sums.  The workspace is exactly what the query asks for, followed by a guard that must survive.
+    N, H, W, Cin, Cout = shape
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape) + 3)
+    dw_ref, db_ref = R.conv3x3_bwd_weight(d["x"], d["dy"])
+    for dtype in (B.F32, B.BF16):
+        need = B.vgg_conv3x3_bwd_weight_workspace_bytes(dtype, N, H, W, Cin, Cout)
+        buf = torch.full((need + 4096,), 0xA5, dtype=torch.uint8, device="cuda")
+        cp = B.vgg_padded_channels(dtype, Cin)
+        dwp = torch.full((9, Cout, cp), float("nan"), device="cuda")
+        db = torch.empty((Cout,), device="cuda")
+        B.vgg_conv3x3_bwd_weight(dtype, N, H, W, Cin, Cout, to_nhwc(d["x"], dtype), to_nhwc(d["dy"], dtype), dwp, db, buf[:need])
+        torch.cuda.synchronize()
+        assert (buf[need:] == 0xA5).all(), dtype
+        dw = dwp[:, :, :Cin].reshape(3, 3, Cout, Cin).permute(2, 3, 0, 1)
+        assert max_rel_err(dw.cpu().numpy(), dw_ref) <= TOL[dtype]
+        assert max_rel_err(db.cpu().numpy(), db_ref) <= TOL[dtype]
+        with pytest.raises(B.VggError):
+            B.vgg_conv3x3_bwd_weight(dtype, N, H, W, Cin, Cout, to_nhwc(d["x"], dtype), to_nhwc(d["dy"], dtype), dwp, db,
+                                     buf[:need - 256])
+
+
+def test_paper_dense_and_softmax_examples():
+    # The paper's two introductory functions at the sizes its compiled listings show: dense on a 10 x 10
+    # matrix, a 10-vector and a 10-vector bias; softmax of a 10-vector (section "Two simple examples").
+    rng = np.random.default_rng(1810)
+    W = rng.standard_normal((10, 10)).astype(np.float32)
+    x = rng.standard_normal((1, 10)).astype(np.float32)
+    b = rng.standard_normal(10).astype(np.float32)
+    z = torch.empty((1, 10), device="cuda")
+    B.vgg_fc(B.F32, 1, 10, 10, dev(x), dev(W), dev(b), z, B.F32, 0, ws_bytes(B.vgg_fc_workspace_bytes(B.F32, 1, 10, 10)))
+    p = torch.empty((1, 10), device="cuda")
+    B.vgg_softmax(1, 10, z, p)
+    torch.cuda.synchronize()
+    zr = R.fc(x, W, b, relu=False)
+    assert max_rel_err(z.cpu().numpy(), zr) <= 1e-6
+    assert np.abs(z.cpu().numpy().astype(np.float64) - (W.astype(np.float64) @ x[0].astype(np.float64) + b)).max() <= 1e-5
+    assert max_rel_err(p.cpu().numpy(), R.softmax(zr)) <= 1e-6
+    assert abs(float(p.sum()) - 1.0) <= 1e-6
+
+
 @pytest.mark.parametrize("shape", RANDOM_CONV_SHAPES)
 def test_conv3x3_random_shapes(shape):
     for dtype in (B.F32, B.BF16):
@@ -250,7 +293,11 @@ def test_maxpool_ties_pick_first():
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200)])
+@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200),
+                                   # rows that are not whole 64-byte units: the paper's own dense example
+                                   # (a 10 x 10 matrix times a 10-vector, here also on ten vectors), odd
+                                   # lengths, a last unit holding one element
+                                   (1, 10, 10), (10, 10, 10), (3, 50, 7), (5, 37, 130), (129, 1, 3), (4, 8200, 40), (6, 2052, 9)])
 def test_fc_forward(dtype, shape):
     N, In, Out = shape
     rng = np.random.default_rng(sum(shape))
@@ -267,10 +314,16 @@ def test_fc_forward(dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200), (113, 160, 33), (250, 96, 72)])
+@pytest.mark.parametrize("shape", [(100, 512, 1000), (2, 512, 10), (7, 2048, 96), (130, 64, 200), (113, 160, 33), (250, 96, 72),
+                                   (1, 10, 10), (10, 10, 10), (5, 37, 130), (9, 50, 64), (3, 1030, 5), (10, 24, 10)])
 def test_fc_backward(dtype, shape):
     # bf16: a and w are bf16, dz fp32 (rounded to bf16 inside, except for db); all results fp32
     N, In, Out = shape
+    if dtype == B.BF16 and In % 8:
+        a = torch.zeros((64,), device="cuda")
+        with pytest.raises(B.VggError):      # 16-byte segments of bf16 rows
+            B.vgg_fc_bwd(dtype, N, In, Out, a, a, a, a, None, None, 0, a)
+        return
     rng = np.random.default_rng(sum(shape) + 5)
     a = rng.standard_normal((N, In)).astype(np.float32)
     w = (rng.standard_normal((Out, In)) * np.sqrt(2.0 / In)).astype(np.float32)
@@ -293,7 +346,7 @@ def test_fc_backward(dtype, shape):
         B.vgg_fc_bwd(dtype, N, In, Out, ad, wd, dev(dz), dw, None, da, 1, None)
 
 
-@pytest.mark.parametrize("shape", [(100, 1000), (2, 10), (5, 64), (3, 129)])
+@pytest.mark.parametrize("shape", [(100, 1000), (2, 10), (5, 64), (3, 129), (1, 10), (1, 1), (4, 5000)])
 def test_softmax_xent_sgd(shape):
     N, K = shape
     rng = np.random.default_rng(N * K)
