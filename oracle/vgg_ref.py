@@ -194,7 +194,7 @@ def round_bf16(a) -> np.ndarray:
 # --------------------------------------------------------------------------
 
 def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: Sequence,
-                  keep: bool = False, operand_round=None) -> Dict[str, object]:
+                  keep: bool = False, operand_round=None, progress=None) -> Dict[str, object]:
     """images [N,3,H,W] -> logits, probs (and every intermediate when keep).
 
     Order of operations: for each of the 16 convolutions, cross-correlate,
@@ -206,8 +206,12 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
     operands: it is applied to everything that enters a product (the images,
     every weight tensor, every layer's output after its ReLU); biases, sums,
     the logits and the softmax stay in full precision.
+
+    ``progress`` (optional) is called with a short text after every layer, for
+    callers that must show signs of life during a long run.
     """
     rd = operand_round if operand_round is not None else (lambda a: a)
+    say = progress if progress is not None else (lambda text: None)
     assert len(conv_w) == 16 and len(fc_w) == 3
     out: Dict[str, object] = {}
     acts: List[np.ndarray] = []      # input of every conv layer
@@ -229,6 +233,7 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
             h, a = maxpool2x2(h)
             if keep:
                 args[l] = a
+        say("oracle forward: convolution %d done" % l)
     N = h.shape[0]
     flat = h.reshape(N, -1)
     pre1 = fc(flat, rd(fc_w[0]), fc_b[0], relu=False)
@@ -244,24 +249,13 @@ def vgg19_forward(x, conv_w: Sequence, conv_b: Sequence, fc_w: Sequence, fc_b: S
     return out
 
 
-def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: float = 0.0,
-                    pool_second_within: float = 0.0, operand_round=None) -> Dict[str, object]:
-    """Backward sweep from a kept forward pass ``f`` (vgg19_forward(keep=True)).
-
-    With the defaults this is the gradient of the mean softmax cross-entropy:
-    ReLU passes gradient where its output is strictly positive, a pool routes
-    its gradient to the recorded first maximum, and the first convolution's
-    input gradient is not formed (the paper's optimised backward pass has 47
-    convolutions, not 48).
-
-    The two optional arguments produce the neighbours of that gradient which
-    a lower-precision evaluation of the same forward pass may legitimately
-    return, because a ReLU or a window maximum is a discrete decision taken on
-    a floating-point value: with ``mask_shift`` t != 0 every ReLU passes
-    gradient where its pre-activation exceeds t * max|pre-activation| of its
-    layer instead of 0 (t may be negative); with ``pool_second_within`` r > 0
-    every pooling window whose two largest values differ by less than
-    r * max(y) routes its gradient to the second of them instead of the first.
+def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, operand_round=None, progress=None) -> Dict[str, object]:
+    """Backward sweep from a kept forward pass ``f`` (vgg19_forward(keep=True)):
+    the gradient of the mean softmax cross-entropy.  A ReLU passes gradient
+    where its pre-activation (``f["conv_pre"]``, ``f["fc_pre"]``) is strictly
+    positive, a pool routes its gradient to the recorded first maximum
+    (``f["pool_arg"]``), and the first convolution's input gradient is not
+    formed (the paper's optimised backward pass has 47 convolutions, not 48).
 
     ``operand_round`` as in vgg19_forward (f must come from a forward pass with
     the same setting): the gradient that enters the convolution stack and the
@@ -269,13 +263,13 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     weights a data gradient multiplies with (convolution and dense) and the
     gradient with respect to a dense layer's pre-activation where it enters
     one of that layer's two backward products; sums (bias gradients
-    included) are not rounded.
+    included) are not rounded.  ``progress`` as in vgg19_forward.
     """
     rd = operand_round if operand_round is not None else (lambda a: a)
+    say = progress if progress is not None else (lambda text: None)
+
     def relu_mask(pre, d):
-        if mask_shift == 0.0:
-            return np.where(pre > 0.0, d, 0.0)
-        return np.where(pre > mask_shift * np.abs(pre).max(), d, 0.0)
+        return np.where(pre > 0.0, d, 0.0)
 
     loss, dlogits = softmax_xent(f["probs"], labels)
     dfc_w = [None] * 3
@@ -296,46 +290,13 @@ def vgg19_gradients(f: Dict[str, object], labels, conv_w, fc_w, mask_shift: floa
     dconv_b = [None] * 16
     for l in range(15, -1, -1):
         if l in _POOL_AFTER:
-            arg = f["pool_arg"][l]
-            if pool_second_within > 0.0:
-                arg = _second_best_where_close(f["conv_out"][l], arg, pool_second_within)
-            d = maxpool2x2_bwd(d, arg)
+            d = maxpool2x2_bwd(d, f["pool_arg"][l])
         g = relu_mask(f["conv_pre"][l], d)
         dconv_w[l], dconv_b[l] = conv3x3_bwd_weight(f["conv_in"][l], g)
         if l > 0:
             d = rd(conv3x3_bwd_data(g, rd(conv_w[l])))
+        say("oracle backward: convolution %d done" % l)
     return dict(loss=loss, dconv_w=dconv_w, dconv_b=dconv_b, dfc_w=dfc_w, dfc_b=dfc_b)
-
-
-def _windows(y):
-    N, Cc, H, W = y.shape
-    return y.reshape(N, Cc, H // 2, 2, W // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, Cc, H // 2, W // 2, 4)
-
-
-def _second_best_where_close(y, arg, rel):
-    win = _windows(y)
-    order = np.argsort(-win, axis=-1, kind="stable")
-    top = np.take_along_axis(win, order[..., :2], axis=-1)
-    close = (top[..., 0] - top[..., 1] < rel * np.abs(y).max()) & (top[..., 0] > 0)
-    out = arg.copy()
-    out[close] = order[..., 1][close].astype(np.uint8)
-    return out
-
-
-def decision_margins(f: Dict[str, object]) -> Dict[str, float]:
-    """How far the forward pass ``f`` (keep=True) is from a different discrete
-    decision: the smallest |pre-activation| of any ReLU and the smallest gap
-    between the two largest values of any pooling window with a positive
-    maximum, each relative to the largest magnitude in its layer."""
-    relu = min(float(np.abs(p).min() / np.abs(p).max()) for p in list(f["conv_pre"]) + list(f["fc_pre"]))
-    pool = 1.0
-    for l in _POOL_AFTER:
-        y = f["conv_out"][l]
-        win = np.sort(_windows(y), axis=-1)
-        gap = (win[..., 3] - win[..., 2])[win[..., 3] > 0]
-        if gap.size:
-            pool = min(pool, float(gap.min() / np.abs(y).max()))
-    return {"relu": relu, "pool": pool}
 
 
 def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01, operand_round=None) -> Dict[str, object]:
@@ -343,7 +304,7 @@ def vgg19_train_step(x, labels, conv_w, conv_b, fc_w, fc_b, lr: float = 0.01, op
 
     Returns loss, logits, probs, the 38 gradient tensors (dconv_w/dconv_b/
     dfc_w/dfc_b), the updated parameters (new_*) and the kept forward pass
-    (``fwd``) for vgg19_gradients / decision_margins.  With ``operand_round``
+    (``fwd``, the input of vgg19_gradients).  With ``operand_round``
     the update is applied to the unrounded (master) parameters.
     """
     f = vgg19_forward(x, conv_w, conv_b, fc_w, fc_b, keep=True, operand_round=operand_round)

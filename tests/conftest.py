@@ -4,12 +4,16 @@ import sys
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
+for _p in (ROOT, os.path.dirname(os.path.abspath(__file__))):
+    if _p not in sys.path:
+        sys.path.insert(0, _p)
 
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # lets a long test print a line past pytest's output capture (see gpu_util.progress)
+    import gpu_util
+    gpu_util.CAPTURE_MANAGER = config.pluginmanager.getplugin("capturemanager")
 
 
 def _have_gpu() -> bool:

@@ -40,3 +40,27 @@ def max_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 def ws_bytes(n: int) -> torch.Tensor:
     return torch.empty((max(int(n), 16),), dtype=torch.uint8, device="cuda")
+
+
+CAPTURE_MANAGER = None   # set by conftest.py
+
+
+def progress(text: str) -> None:
+    """Sign of life from inside a long test (the oracle at full size runs for minutes without a test
+    ending): one line on the real stdout, past pytest's capture, and in a log under the run-output folder."""
+    import os
+    import sys
+    import time
+    line = "%s %s" % (time.strftime("%H:%M:%S"), text)
+    if CAPTURE_MANAGER is not None:
+        with CAPTURE_MANAGER.global_and_fixture_disabled():
+            sys.stdout.write("\n[progress] " + line + "\n")
+            sys.stdout.flush()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = os.path.join(root, "gpurun_out")
+    try:
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "test_progress.log"), "a") as fh:
+            fh.write(line + "\n")
+    except OSError:
+        pass
