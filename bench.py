@@ -238,6 +238,42 @@ def batch_sweep(dtype_name, batches, steps):
     return res
 
 
+def conv_microbench(steps):
+    """configs[1]: one conv3_1-style layer, fp32, 128 -> 256 channels, 56x56, batch 100, bias + ReLU, through the
+    single-operation entry point; N(0,1) inputs, He-normal weights.  ms, TFLOP/s and share of the fp32 MFMA peak."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    from paper_1810_09868_amd import synth
+    N, H, W, Cin, Cout = 100, 56, 56, 128, 256
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=0)
+    xs = torch.from_numpy(d["x"]).cuda()
+    x = torch.empty((N, H, W, Cin), dtype=torch.float32, device="cuda")
+    B.vgg_nchw_to_nhwc(B.F32, N, Cin, H, W, Cin, xs, x)
+    wp = torch.empty((9, Cout, Cin), dtype=torch.float32, device="cuda")
+    B.vgg_conv_pack_weights(B.F32, Cin, Cout, torch.from_numpy(d["w"]).cuda(), wp, 0)
+    bias = torch.from_numpy(d["b"]).cuda()
+    y = torch.empty((N, H, W, Cout), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        B.vgg_conv3x3_fwd(B.F32, N, H, W, Cin, Cout, x, wp, bias, y, 1, None)
+    # (the binding launches on torch's current stream, which is the stream these events are recorded on)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        B.vgg_conv3x3_fwd(B.F32, N, H, W, Cin, Cout, x, wp, bias, y, 1, None)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    flops = 2.0 * N * H * W * 9 * Cin * Cout
+    tf = flops / (ms * 1e-3) / 1e12
+    byts = 4.0 * (N * H * W * (Cin + Cout) + 9 * Cin * Cout)
+    return {"workload": "configs[1]: 3x3 conv 128->256, 56x56, batch 100, fp32, bias+ReLU (vgg_conv3x3_fwd)",
+            "dtype": "f32", "ms": round(ms, 4), "gflop": round(flops / 1e9, 2), "tflops": round(tf, 2),
+            "pct_fp32_mfma_peak": round(100.0 * tf / PEAK_TFLOPS["f32"], 2),
+            "min_bytes_mb": round(byts / 1e6, 1), "gbs_at_min_bytes": round(byts / (ms * 1e-3) / 1e9, 1)}
+
+
 def mfma_loop_ceiling():
     """TFLOP/s of a loop of nothing but MFMAs (register operands), constant and random operands: what the chip
     sustains at the clock it holds under matrix load, next to the data-sheet peak used for `roofline.peak`."""
@@ -337,7 +373,9 @@ def main():
         out["secondary"] = {"workload": "configs[2] fp32" if other == "f32" else "configs[3] bf16",
                             "dtype": other, "images_per_s": sec["images_per_s"], "ms_per_step": sec["ms_per_step"],
                             "conv_tflops": sec["conv_tflops"], "pct_mfma_peak_conv": sec["pct_mfma_peak_conv"],
-                            "roofline": sec["roofline"]}
+                            "conv_ms_per_step": sec["conv_ms_per_step"], "other_ms_per_step": sec["other_ms_per_step"],
+                            "per_layer": sec["per_layer"], "roofline": sec["roofline"]}
+        out["conv_microbenchmark"] = conv_microbench(max(5, a.steps))
     if not a.no_secondary:
         out["train_step"] = run_train_bench(a.batch, max(2, a.steps // 5))
         out["train_step_bf16"] = run_train_bench(a.batch, max(2, a.steps // 2), dtype_name="bf16", extras=False)

@@ -19,6 +19,12 @@
  *    synchronises: every call only enqueues kernels on `stream` (a
  *    hipStream_t passed as void*; NULL is the default stream).  Buffers are
  *    owned by the caller and must stay alive until the stream has drained.
+ *    One exception: the first launch of a convolution or weight-gradient
+ *    kernel in a process raises that kernel's dynamic-LDS limit
+ *    (hipFuncSetAttribute), which is a host-side call and not a stream
+ *    operation.  It is serialised inside the library, so entry points may be
+ *    called from several host threads; but run every call once before
+ *    recording it into a HIP graph.
  *  - Tensor pointers must be 16-byte aligned (VGG_ERR_ALIGN otherwise).
  *  - dtype: VGG_F32 = activations and weights fp32, fp32 MFMA.
  *           VGG_BF16 = activations and weights bf16 (round-to-nearest-even

@@ -4,8 +4,24 @@
 #include "common.h"
 #include "flip_jobs.h"
 
+#include <mutex>
+
+#include <map>
 
 namespace vgg {
+
+bool raise_lds_limit(const void *kernel)
+{
+    // kernels whose limit has been raised in this process; guarded: entry points may be called from several threads
+    static std::mutex mu;
+    static std::map<const void *, bool> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count(kernel)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
+    done[kernel] = true;
+    return true;
+}
+
 // kernels' host launchers (defined in the other translation units)
 int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void *x, const void *w, const float *bias,
                   const void *mask, void *y, void *pool, unsigned char *argmax, int relu, void *part_ws, hipStream_t stream);

@@ -21,6 +21,11 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int dtype_size(int dtype) { return dtype == VGG_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dtype) { return dtype == VGG_F32 || dtype == VGG_BF16; }
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per process
+// (hipFuncSetAttribute, not a stream operation).  Idempotent, so concurrent first calls are harmless;
+// the flag only saves the repeated call.  Defined in api.hip.
+bool raise_lds_limit(const void *kernel);
+
 // Maps the HIP error state after enqueueing to a status code.
 inline int launch_status() { return hipGetLastError() == hipSuccess ? VGG_OK : VGG_ERR_LAUNCH; }
 

@@ -12,13 +12,17 @@
 // the halo leaves the image, and is then read by all nine taps, so zero
 // padding and image boundaries inside a tile need no masks.
 //
-// Every LDS row holds 64 bytes of one pixel's channels (16 fp32 or 32 bf16)
-// plus 16 bytes of padding, which makes the 16-byte fragment reads of 32
-// consecutive rows bank-conflict free.  A lane reads 16 bytes of A and of B
-// at the same (k-group, k-half) position: for bf16 that is the 8-element
-// operand of one v_mfma_f32_32x32x16_bf16; for fp32 the four elements feed
-// four v_mfma_f32_32x32x2_f32 (any fixed pairing of k indices between A and B
-// is a valid contraction order).
+// Every LDS row holds 64 bytes of one pixel's channels (16 fp32 or 32 bf16).
+// Two row layouts keep the 16-byte fragment reads of consecutive rows on
+// distinct banks: rows padded to 80 bytes (the register-staged kernel below,
+// and the halo of the 8-wave direct-to-LDS kernel with up to 384 halo rows),
+// or unpadded 64-byte rows whose 16-byte segments are XOR-swizzled with the
+// row number (all weight rows of the direct-to-LDS kernels, and the halo of
+// their other variants).  A lane reads 16 bytes of A and of B at the same
+// (k-group, k-half) position: for bf16 that is the 8-element operand of one
+// v_mfma_f32_32x32x16_bf16; for fp32 the four elements feed four
+// v_mfma_f32_32x32x2_f32 (any fixed pairing of k indices between A and B is a
+// valid contraction order).
 #include "common.h"
 
 namespace vgg {
@@ -259,8 +263,8 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
     }
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NBUF>
-__global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)) void conv3x3_igemm_kernel(ConvArgs p)
+template <typename T, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 2) void conv3x3_igemm_kernel(ConvArgs p)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;  // 32x32 MFMA tiles per wave along pixels
@@ -271,10 +275,8 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
     const int S = p.g.S;
     const int SA = p.rowsA;                     // rows reserved for the halo (>= S)
     int *pix = reinterpret_cast<int *>(smem);   // [SA] halo row -> input pixel or -1
-    char *As = smem + round_up16(SA * 4);              // [NBUF][SA][80]
-    char *Bs = As + (size_t)NBUF * SA * kRowBytes;     // [NBUF][3][BN][80]
-    const int a_bytes = SA * kRowBytes;
-    constexpr int b_bytes = 3 * BN * kRowBytes;
+    char *As = smem + round_up16(SA * 4);              // [SA][80]
+    char *Bs = As + (size_t)SA * kRowBytes;            // [3][BN][80]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
@@ -389,26 +391,24 @@ __global__ __launch_bounds__(WM *WN * 64, NBUF == 2 ? 1 : (WM * WN == 8 ? 4 : 2)
     };
 
     // Software pipeline: the global loads of stage s+1 are issued before the MFMAs of stage s and
-    // land in LDS after them, so their latency is covered by the arithmetic.  With NBUF == 2 they
-    // land in the other LDS buffer and one barrier per stage is enough.
-    int kh = 0, c0 = 0, ab = 0, bb = 0;
+    // land in LDS after them (two barriers per stage), so their latency is covered by the arithmetic.
+    int kh = 0, c0 = 0;
     for (int s = 0; s + 1 < nstages; ++s) {
         int nkh = kh + 1, nc0 = c0;
         if (nkh == 3) { nkh = 0; nc0 += KC; }
         const bool new_chunk = nkh == 0;
         load_b(nc0, nkh, breg);
         if (new_chunk && a_regs) load_a(nc0, areg);
-        compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
-        if (NBUF == 1) __syncthreads();  // every wave is done reading this stage's LDS data
-        const int nab = NBUF == 2 && new_chunk ? ab ^ 1 : ab, nbb = NBUF == 2 ? bb ^ 1 : bb;
-        store_b(breg, Bs + nbb * b_bytes);
+        compute(kh, As, Bs);
+        __syncthreads();  // every wave is done reading this stage's LDS data
+        store_b(breg, Bs);
         if (new_chunk) {
-            if (a_regs) store_a(areg, As + nab * a_bytes); else copy_a_direct(nc0, As + nab * a_bytes);
+            if (a_regs) store_a(areg, As); else copy_a_direct(nc0, As);
         }
         __syncthreads();
-        kh = nkh; c0 = nc0; ab = nab; bb = nbb;
+        kh = nkh; c0 = nc0;
     }
-    compute(kh, As + ab * a_bytes, Bs + bb * b_bytes);
+    compute(kh, As, Bs);
 
     conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
@@ -615,18 +615,12 @@ static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t st
     size_t lds = (size_t)a.rowsA * 4 + (size_t)a.rowsA * arow_bytes + (size_t)2 * 3 * BN * kDataBytes;
     if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
     auto kern = conv3x3_igemm_dma_kernel<T, BM, BN, WM, WN, SA>;
-    static bool configured = false;
-    if (lds > 64 * 1024 && !configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                160 * 1024) != hipSuccess)
-            return VGG_ERR_LAUNCH;
-        configured = true;
-    }
+    if (lds > 64 * 1024 && !raise_lds_limit(reinterpret_cast<const void *>(kern))) return VGG_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n * a.ksplit)), dim3(WM * WN * 64), lds, stream, a);
     return launch_status();
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NBUF>
+template <typename T, int BM, int BN, int WM, int WN>
 static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stream)
 {
     ConvArgs a = a0;
@@ -634,17 +628,11 @@ static int launch_conv(const ConvArgs &a0, int N, int H, int W, hipStream_t stre
     a.tiles_n = (a.Cout + BN - 1) / BN;
     constexpr int NT = WM * WN * 64;
     a.rowsA = a.g.S * 4 <= kMaxAHaloSegsPerBlock ? kMaxAHaloSegsPerBlock / 4 : a.g.S;
-    size_t lds = round_up((size_t)a.rowsA * 4, 16) + (size_t)NBUF * ((size_t)a.rowsA * kRowBytes + (size_t)3 * BN * kRowBytes);
+    size_t lds = round_up((size_t)a.rowsA * 4, 16) + (size_t)a.rowsA * kRowBytes + (size_t)3 * BN * kRowBytes;
     if (lds < (size_t)WM * WN * kEpiBytes) lds = (size_t)WM * WN * kEpiBytes;
     if (lds > 160 * 1024) return VGG_ERR_UNSUPPORTED;
-    auto kern = conv3x3_igemm_kernel<T, BM, BN, WM, WN, NBUF>;
-    static bool configured = false;
-    if (lds > 64 * 1024 && !configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                160 * 1024) != hipSuccess)
-            return VGG_ERR_LAUNCH;
-        configured = true;
-    }
+    auto kern = conv3x3_igemm_kernel<T, BM, BN, WM, WN>;
+    if (lds > 64 * 1024 && !raise_lds_limit(reinterpret_cast<const void *>(kern))) return VGG_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n)), dim3(WM * WN * 64), lds, stream, a);
     return launch_status();
 }
@@ -777,8 +765,8 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
             rc = narrow ? launch_conv_dma<float, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
                         : launch_conv_dma<float, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
         else
-            rc = narrow ? launch_conv<float, 256, 64, 4, 1, 1>(a, N, H, W, stream)
-                        : launch_conv<float, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+            rc = narrow ? launch_conv<float, 256, 64, 4, 1>(a, N, H, W, stream)
+                        : launch_conv<float, 256, 128, 4, 2>(a, N, H, W, stream);
     } else {
         if (dma)
             rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
@@ -787,8 +775,8 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
             rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRowsBig>(a, g, stream)
                         : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRowsBig>(a, g, stream);
         else
-            rc = narrow ? launch_conv<bf16_t, 256, 64, 4, 1, 1>(a, N, H, W, stream)
-                        : launch_conv<bf16_t, 256, 128, 4, 2, 1>(a, N, H, W, stream);
+            rc = narrow ? launch_conv<bf16_t, 256, 64, 4, 1>(a, N, H, W, stream)
+                        : launch_conv<bf16_t, 256, 128, 4, 2>(a, N, H, W, stream);
     }
     if (rc != VGG_OK || c.ksplit == 1) return rc;
     const size_t quads = (size_t)N * H * W * Cout / 4;

@@ -574,19 +574,12 @@ int conv3x3_wgrad(int N, int H, int W, int Cin, int CinP, int Cout, const float 
     const size_t red = (size_t)2 * 9 * 16 * 64 * 4 + 64 * 4;
     if (lds < red) lds = red;
     if (lds > 160 * 1024) return VGG_ERR_UNSUPPORTED;
-    static bool configured = false;
-    if (lds > 64 * 1024 && !configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<14>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_wgrad_thin_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return VGG_ERR_LAUNCH;
-        configured = true;
-    }
+    if (lds > 64 * 1024 &&
+        !(raise_lds_limit(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<0>)) &&
+          raise_lds_limit(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<16>)) &&
+          raise_lds_limit(reinterpret_cast<const void *>(conv3x3_wgrad_kernel<14>)) &&
+          raise_lds_limit(reinterpret_cast<const void *>(conv3x3_wgrad_thin_kernel))))
+        return VGG_ERR_LAUNCH;
     const dim3 grid((unsigned)(a.tiles_co * a.tiles_ci * a.splits));
     if (thin)
         hipLaunchKernelGGL(conv3x3_wgrad_thin_kernel, grid, dim3(kWaves * 64), lds, stream, a, Cin);
