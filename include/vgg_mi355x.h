@@ -58,7 +58,8 @@ typedef enum vgg_status {
     VGG_ERR_ALIGN = -4,       /* a tensor pointer is not 16-byte aligned */
     VGG_ERR_WORKSPACE = -5,   /* ws is NULL or ws_bytes too small */
     VGG_ERR_LAUNCH = -6,      /* HIP reported an error when a kernel was enqueued */
-    VGG_ERR_UNSUPPORTED = -7  /* valid request the library does not implement (e.g. bf16 training without master copy) */
+    VGG_ERR_UNSUPPORTED = -7, /* valid request the library does not implement (e.g. bf16 training without master copy) */
+    VGG_ERR_TOO_LARGE = -8    /* vgg_fc_static: the problem needs more scratch than the built-in buffer holds */
 } vgg_status;
 
 typedef enum vgg_dtype { VGG_F32 = 0, VGG_BF16 = 1 } vgg_dtype;
@@ -217,6 +218,27 @@ int vgg_maxpool2x2_bwd(int dtype, int N, int H, int W, int C, const void *dy_nhw
 size_t vgg_fc_workspace_bytes(int dtype, int N, int In, int Out);
 int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias,
            void *z, int z_dtype, int relu, void *ws, size_t ws_bytes, void *stream);
+
+/* vgg_fc for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results
+ * as vgg_fc, but no ws: the partial sums of the split contraction go to a
+ * buffer of VGG_FC_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (every GPU the library is used on holds its own copy until the
+ * process ends).  Calls no hipMalloc / hipFree and no allocating routine.
+ * Returns VGG_ERR_TOO_LARGE, before touching the device, when
+ * vgg_fc_workspace_bytes(dtype, N, In, Out) exceeds the buffer (the network's
+ * three dense layers at batch 100 fit: 26.2 MB for 25088 -> 4096).
+ * All calls on one GPU share that GPU's buffer: calls that may overlap on one
+ * GPU (different streams, different host threads) race; calls on one stream
+ * are ordered and safe.  The buffer keeps the previous call's partial sums;
+ * every value a call reads it has written first, so nothing needs clearing.
+ * The first call on a device looks the buffer's address up
+ * (hipGetSymbolAddress), which is not a stream operation: make one call
+ * before starting a graph capture. */
+#define VGG_FC_STATIC_SCRATCH_BYTES (32u << 20)
+int vgg_fc_static(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias,
+                  void *z, int z_dtype, int relu, void *stream);
 
 /* dw[o,i] = sum_n dz[n,o] a[n,i]; db[o] = sum_n dz[n,o] (db may be NULL); if
  * da is non-NULL, da[n,i] = sum_o dz[n,o] w[o,i], multiplied by (a[n,i] > 0)

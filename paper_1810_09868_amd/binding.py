@@ -29,6 +29,7 @@ EXPORTS = [
     "vgg19_packed_bytes", "vgg19_forward_workspace_bytes", "vgg19_train_workspace_bytes",
     "vgg19_pack_params", "vgg19_unpack_params", "vgg19_forward", "vgg19_train_step", "vgg19_plan",
     "vgg19_timed", "vgg_mfma_probe_sink_bytes", "vgg_mfma_probe", "vgg_conv3x3_plan",
+    "vgg_fc_static",
 ]
 
 
@@ -85,6 +86,7 @@ def lib() -> C.CDLL:
             getattr(L, n).restype = _sz
             getattr(L, n).argtypes = [_i] * 4
         L.vgg_fc.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _i, _i, _vp, _sz, _vp]
+        L.vgg_fc_static.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _i, _i, _vp]
         L.vgg_fc_bwd.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
         L.vgg_softmax.argtypes = [_i, _i, _vp, _vp, _vp]
         L.vgg_softmax_xent_bwd.argtypes = [_i, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -224,6 +226,14 @@ def vgg_fc_workspace_bytes(dtype, N, In, Out) -> int:
 def vgg_fc(dtype, N, In, Out, a, w, bias, z, z_dtype, relu, ws):
     _chk(lib().vgg_fc(dtype, N, In, Out, _ptr(a), _ptr(w), _ptr(bias), _ptr(z), z_dtype, int(relu), _ptr(ws),
                       _nbytes(ws), _stream()), "vgg_fc")
+
+
+FC_STATIC_SCRATCH_BYTES = 32 << 20  # VGG_FC_STATIC_SCRATCH_BYTES
+
+
+def vgg_fc_static(dtype, N, In, Out, a, w, bias, z, z_dtype, relu):
+    _chk(lib().vgg_fc_static(dtype, N, In, Out, _ptr(a), _ptr(w), _ptr(bias), _ptr(z), z_dtype, int(relu), _stream()),
+         "vgg_fc_static")
 
 
 def vgg_fc_bwd_workspace_bytes(dtype, N, In, Out) -> int:

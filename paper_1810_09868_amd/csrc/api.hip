@@ -464,6 +464,7 @@ const char *vgg_strerror(int status)
     case VGG_ERR_WORKSPACE: return "workspace missing or too small";
     case VGG_ERR_LAUNCH: return "kernel launch failed";
     case VGG_ERR_UNSUPPORTED: return "unsupported request";
+    case VGG_ERR_TOO_LARGE: return "problem needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }
@@ -674,6 +675,47 @@ int vgg_fc(int dtype, int N, int In, int Out, const void *a, const void *w, cons
     if (!aligned16(a) || !aligned16(w) || !aligned16(z) || (ws && !aligned16(ws))) return VGG_ERR_ALIGN;
     if (!ws || ws_bytes < fc_workspace(dtype, N, In, Out)) return VGG_ERR_WORKSPACE;
     return fc_forward(dtype, N, In, Out, a, w, bias, z, z_dtype, relu ? 1 : 0, ws, (hipStream_t)stream);
+}
+
+// ---- vgg_fc for callers that cannot allocate: the partial sums of the split contraction go to a buffer
+// that is part of the library's device image instead of a caller's workspace.
+static __device__ __align__(256) unsigned char scratch[VGG_FC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];   // per device: address of that device's copy of `scratch`
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of the buffer, looked up once per device.  (In host code the
+// array's name is only a handle for this lookup, never an address a kernel could use.)
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VGG_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return VGG_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return VGG_OK;
+}
+}  // namespace
+
+int vgg_fc_static(int dtype, int N, int In, int Out, const void *a, const void *w, const float *bias, void *z, int z_dtype,
+                  int relu, void *stream)
+{
+    if (!a || !w || !z) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype) || !dtype_ok(z_dtype)) return VGG_ERR_DTYPE;
+    if (N <= 0 || In <= 0 || Out <= 0) return VGG_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(z)) return VGG_ERR_ALIGN;
+    if (fc_workspace(dtype, N, In, Out) > (size_t)VGG_FC_STATIC_SCRATCH_BYTES) return VGG_ERR_TOO_LARGE;
+    void *ptr = nullptr;
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != VGG_OK) return rc;
+    // (every partial sum the second kernel reads is written by the first: nothing to clear between calls)
+    return fc_forward(dtype, N, In, Out, a, w, bias, z, z_dtype, relu ? 1 : 0, ptr, (hipStream_t)stream);
 }
 
 size_t vgg_fc_bwd_workspace_bytes(int dtype, int N, int In, int Out)

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_strerror_and_padded_channels():
     L = B.lib()
     assert L.vgg_strerror(0) == b"ok"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert L.vgg_strerror(code) not in (b"ok", b"unknown status")
     assert B.vgg_padded_channels(B.F32, 3) == 16
     assert B.vgg_padded_channels(B.BF16, 3) == 32
@@ -57,6 +57,12 @@ def test_argument_validation_happens_on_the_host():
     assert L.vgg_fc(0, 10, 10, 10, a, a, None, a, 0, 0, None, 0, None) == -5             # any In is a valid shape
     assert L.vgg_fc_bwd(1, 2, 12, 8, a, a, a, a, None, None, 0, a, 1 << 30, None) == -7  # bf16 backward: In % 8
     assert L.vgg_fc(0, 2, 64, 8, a, a, None, a, 0, 0, None, 0, None) == -5
+    # the variant without a workspace argument: what exceeds its built-in buffer is refused on the host
+    assert B.vgg_fc_workspace_bytes(B.F32, 1100, 8192, 4096) > B.FC_STATIC_SCRATCH_BYTES
+    assert L.vgg_fc_static(0, 1100, 8192, 4096, a, a, None, a, 0, 0, None) == -8
+    assert L.vgg_fc_static(0, 0, 8192, 4096, a, a, None, a, 0, 0, None) == -2
+    assert L.vgg_fc_static(0, 4, 64, 8, a + 8, a, None, a, 0, 0, None) == -4
+    assert B.vgg_fc_workspace_bytes(B.F32, 100, 25088, 4096) <= B.FC_STATIC_SCRATCH_BYTES
     assert L.vgg_softmax(0, 10, a, a, None) == -2
     assert L.vgg_sgd_update(0, a, a, 0.1, None) == -2
     assert L.vgg_sgd_update(4, None, a, 0.1, None) == -1
