@@ -34,9 +34,13 @@
  *    batch and canonical parameters (convolution weights [Cout][Cin][3][3],
  *    dense weights [Out][In], the first dense layer's columns in C,H,W
  *    flatten order) and convert once.
- *  - Packed convolution weights: element (tap t = 3*kh+kw, co, ci) lives at
- *    index (t*Cout + co)*CinP + ci with CinP = vgg_padded_channels(dtype, Cin) and
- *    zeros in ci >= Cin.
+ *  - Packed convolution weights, CinP = vgg_padded_channels(dtype, Cin), zeros
+ *    in ci >= Cin, 9*Cout*CinP elements: VGG_F32 keeps element (tap t =
+ *    3*kh+kw, co, ci) at index (t*Cout + co)*CinP + ci.  VGG_BF16 blocks the
+ *    input channels by 16 -- index ((t*(CinP/16) + ci/16)*Cout + co)*16 + ci%16
+ *    -- so that the 32 channels x 16 contraction indices of one matrix
+ *    instruction's operand are 1 KB of contiguous memory.  Gradients and fp32
+ *    master copies are always in the VGG_F32 layout.
  *  - `ws`/`ws_bytes`: caller-owned scratch; the matching *_workspace_bytes
  *    query gives the size required (VGG_ERR_WORKSPACE if smaller).
  */
@@ -107,10 +111,11 @@ int vgg_padded_channels(int dtype, int C);
 
 /* Packs canonical fp32 weights [Cout][Cin][3][3] into the layout described
  * above, converting to `dtype`.  With transpose_flip != 0 it instead writes
- * the operand the data-gradient convolution consumes: element (t, ci, co) at
- * (t*Cin + ci)*CoutP + co holding w[co][ci][8-t] (taps rotated by 180
- * degrees, channel roles swapped; cf. the "reverse" ops of the backward
- * column of the appendix table), CoutP = vgg_padded_channels(dtype, Cout). */
+ * the operand the data-gradient convolution consumes: element (t, ci, co) of
+ * a [Cin][CoutP] matrix per tap, in the same layout with the roles of the
+ * channel counts exchanged, holding w[co][ci][8-t] (taps rotated by 180
+ * degrees; cf. the "reverse" ops of the backward column of the appendix
+ * table), CoutP = vgg_padded_channels(dtype, Cout). */
 int vgg_conv_pack_weights(int dtype, int Cin, int Cout, const float *w_oihw, void *w_packed,
                           int transpose_flip, void *stream);
 /* Inverse of the forward packing for fp32 data (used for gradients and
@@ -323,7 +328,9 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
  * network, vgg_conv3x3_fwd_first, excluded).  Writes VGG_PLAN_INFO_LEN ints to
  * info_host (host memory, cap >= VGG_PLAN_INFO_LEN else VGG_ERR_SHAPE):
  *   [0] kernel: 0 register-staged implicit GEMM, 1 / 2 / 3 direct-to-LDS
- *       implicit GEMM with room for 384 / 448 / 192 halo rows; weight
+ *       implicit GEMM with room for 384 / 448 / 192 halo rows, 4 / 5 the
+ *       bf16 implicit GEMM with its weights in registers and room for
+ *       384 / 448 halo rows; weight
  *       gradient: 100 linear tiles, 114 / 116 patches 14 / 16 pixels wide,
  *       103 the kernel for at most three input channels (fp32); 116 / 117
  *       the bf16 kernel and its variant for at most 32 input channels

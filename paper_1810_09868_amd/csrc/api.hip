@@ -50,6 +50,7 @@ int softmax_xent_bwd(int N, int K, const float *p, const int32_t *labels, float 
                      hipStream_t s);
 int sgd_update(size_t n, float *theta, const float *grad, float lr, hipStream_t s);
 int sgd_update_master(size_t n, float *theta, const float *grad, float lr, void *copy, int copy_dtype, hipStream_t s);
+int sgd_update_master_conv(SgdConvJobs &jobs, float lr, hipStream_t s);
 int nchw_to_nhwc(int dtype, int N, int C, int H, int W, int Cpad, const float *x, void *y, hipStream_t s);
 int nhwc_to_nchw(int dtype, int N, int C, int H, int W, int Cpad, const void *x, float *y, hipStream_t s);
 int pad_channels(int dtype, size_t pixels, int C, int Cpad, const void *x, void *y, hipStream_t s);
@@ -399,13 +400,20 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
         VGG_STEP(rec, K_OTHER, sgd_update_master(n, F(pm + m_first), F(gr + m_first), c->lr, pk + w_first, copy_dtype, s));
         return true;
     };
-    bool conv_prop = true, fc_prop = true;
-    for (int l = 0; l < VGG19_NUM_CONV; ++l) conv_prop = conv_prop && Pm.conv_w[l] == 2 * P.conv_w[l];
+    bool fc_prop = true;
     for (int l = 0; l < VGG19_NUM_FC; ++l) fc_prop = fc_prop && Pm.fc_w[l] - Pm.fc_w[0] == 2 * (P.fc_w[l] - P.fc_w[0]);
-    if (!(conv_prop && group(Pm.conv_w[0], Pm.conv_b[0], P.conv_w[0], P.conv_b[0], VGG_BF16)))
-        for (int l = 0; l < VGG19_NUM_CONV; ++l)
-            VGG_STEP(rec, K_OTHER, sgd_update_master((size_t)9 * kConvCh[l][1] * P.cinp[l], F(pm + Pm.conv_w[l]),
-                                                     F(gr + Pm.conv_w[l]), c->lr, pk + P.conv_w[l], VGG_BF16, s));
+    {
+        // convolution weights: the bf16 copies are in the blocked layout, the masters row-major
+        SgdConvJobs jobs;
+        jobs.n = VGG19_NUM_CONV;
+        for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+            jobs.theta[l] = F(pm + Pm.conv_w[l]);
+            jobs.grad[l] = F(gr + Pm.conv_w[l]);
+            jobs.copy[l] = reinterpret_cast<unsigned short *>(pk + P.conv_w[l]);
+            jobs.Cout[l] = kConvCh[l][1]; jobs.CinP[l] = P.cinp[l];
+        }
+        VGG_STEP(rec, K_OTHER, sgd_update_master_conv(jobs, c->lr, s));
+    }
     if (!group(Pm.conv_b[0], Pm.fc_w[0], P.conv_b[0], P.fc_w[0], VGG_F32))
         for (int l = 0; l < VGG19_NUM_CONV; ++l)
             VGG_STEP(rec, K_OTHER, sgd_update_master(kConvCh[l][1], F(pm + Pm.conv_b[l]), F(gr + Pm.conv_b[l]), c->lr,

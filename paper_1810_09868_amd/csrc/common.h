@@ -86,6 +86,30 @@ inline int padded_channels(int dtype, int C)
 }
 
 // ---------------------------------------------------------------------------
+// Packed convolution operand: nine taps of a [rows][colsP] matrix whose columns are the contraction
+// index (input channels; colsP a multiple of the padding granularity).
+//   fp32: element (t, row, col) at (t*rows + row)*colsP + col.
+//   bf16: the columns are blocked by 16: element (t, row, col) at
+//         ((t*(colsP/16) + col/16)*rows + row)*16 + col%16,
+//         so that the 32 rows x 16 columns of one v_mfma_f32_32x32x16_bf16 operand are 1 KB of
+//         contiguous memory and a wave can load its fragment straight from global memory.
+// Both have 9*rows*colsP elements.
+// ---------------------------------------------------------------------------
+template <typename T>
+__host__ __device__ __forceinline__ size_t packed_w_index(int t, int row, int col, int rows, int colsP)
+{
+    if (sizeof(T) == 2) return (((size_t)t * (colsP >> 4) + (col >> 4)) * rows + row) * 16 + (col & 15);
+    return ((size_t)t * rows + row) * colsP + col;
+}
+// Byte offset of the 16-byte segment `seg` (0..3) of the 64 bytes of row `row` that start at column c0
+// (a multiple of 16 fp32 / 32 bf16 columns): what one LDS row of the convolution kernels holds.
+template <typename T>
+__host__ __device__ __forceinline__ size_t packed_w_segment(int t, int row, int c0, int seg, int rows, int colsP)
+{
+    return packed_w_index<T>(t, row, c0 + seg * (16 / (int)sizeof(T)), rows, colsP) * sizeof(T);
+}
+
+// ---------------------------------------------------------------------------
 // Tile geometry of the convolution kernels.
 //
 // A tile is a set of up to `rows` output pixels of the NHWC tensor together

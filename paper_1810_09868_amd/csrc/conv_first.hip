@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(FirstArgs p)
     constexpr bool kBf16 = sizeof(T) == 2;
     // filter operand for contraction index k, output channel co (bias at the padding indices)
     auto wval = [&](int k, int co) -> float {
-        if (k < 27) return Elem<T>::load(wp + ((size_t)(k / 3) * kFirstCout + co) * p.CinP + k % 3);
+        if (k < 27) return Elem<T>::load(wp + packed_w_index<T>(k / 3, co, k % 3, kFirstCout, p.CinP));
         const float b = p.bias ? p.bias[co] : 0.f;
         if (k == 27) return kBf16 ? bf16_to_f32(f32_to_bf16(b)) : b;
         if (k == 28 && kBf16) return b - bf16_to_f32(f32_to_bf16(b));

@@ -25,6 +25,9 @@
 // valid contraction order).
 #include "common.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace vgg {
 
 constexpr int kRowBytes = 80;  // 64 data + 16 pad
@@ -349,8 +352,7 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 2) void conv3x3_igem
             const int row = idx >> 2;  // kw*BN + n
             const int kw = row / BN;
             const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
-            breg[j] = *reinterpret_cast<const u32x4 *>(
-                p.w + ((size_t)((kh * 3 + kw) * p.Cout + n) * p.CinP + c0) * sizeof(T) + (idx & 3) * 16);
+            breg[j] = *reinterpret_cast<const u32x4 *>(p.w + packed_w_segment<T>(kh * 3 + kw, n, c0, idx & 3, p.Cout, p.CinP));
         }
     };
     auto store_b = [&](const u32x4(&breg)[NB], char *Bs) __attribute__((always_inline)) {
@@ -479,12 +481,13 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
         const int row = (wv * NB + q) * 16 + (lane >> 2);   // kw*BN + n
         const int kw = row / BN;
         const int n = min(n0 + row - kw * BN, p.Cout - 1);  // columns past Cout are never stored
-        woff[q] = (unsigned)((kw * p.Cout + n) * p.CinP) * (unsigned)sizeof(T) + ((((lane & 3) ^ swz(row))) << 4);
+        // (offset of this lane's source segment from that of tap (kh, 0), row 0, column c0, segment 0)
+        woff[q] = (unsigned)(packed_w_segment<T>(kw, n, 0, (lane & 3) ^ swz(row), p.Cout, p.CinP));
     }
     const unsigned bs_lds = __builtin_amdgcn_readfirstlane(
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)(Bs + wv * NB * 1024));
     auto dma_b = [&](int c0, int kh, int buf) __attribute__((always_inline)) {
-        const char *base = p.w + ((size_t)(kh * 3) * p.Cout * p.CinP + c0) * sizeof(T);
+        const char *base = p.w + packed_w_segment<T>(kh * 3, 0, c0, 0, p.Cout, p.CinP);
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
             // Issued as inline assembly on purpose: the compiler cannot tell that this write and the
@@ -604,6 +607,186 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
     else conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
+// ---------------------------------------------------------------------------
+// bf16 variant with the weight fragments in registers.  The blocked weight layout (packed_w_index)
+// makes the 32 channels x 16 contraction indices of an MFMA operand 1 KB of contiguous memory, so a
+// wave loads its weight fragments straight from global memory (L2), a few MFMA steps ahead, into a
+// small ring of registers; LDS holds only the input halo.  Compared with the kernel above this
+// removes the weights from LDS traffic (half the fragment reads), the per-stage weight copies and
+// their barrier: one barrier per 32-channel chunk, i.e. per 144 MFMAs of a wave.
+//
+// Workgroup: WM x WN waves, each a 128-pixel x 64-channel sub-tile (4 x 2 MFMA blocks, 128
+// accumulator registers), two workgroups per CU.  A chunk is 18 steps (tap, k-group); a step is 4
+// halo-fragment reads and 8 MFMAs.  The halo of a chunk is copied by global_load_lds_dwordx4 into one
+// of two buffers a whole chunk ahead; rows are 80 bytes (64 data + 16 pad, conflict-free fragment
+// reads at addresses that are a per-lane base plus an offset per tap); the copy treats a buffer as
+// consecutive 16-byte slots, slot s = row s / 5, segment s % 5, every lane supplying the source
+// address of its slot (pad slots and rows outside the image read a block of zeros).
+// All vector-memory waits are written by hand (the loads are inline assembly), counting the
+// operations issued since the one waited for; the schedule is static, so the counts are constants.
+// The order of the sums (chunk, kernel row, tap, k-group) is that of the kernel above: results are
+// bit-identical.
+// ---------------------------------------------------------------------------
+constexpr int kWregHaloRows = 384;      // halo rows of the weights-in-registers kernel (64 KB of LDS) ...
+constexpr int kWregHaloRowsBig = 448;   // ... and of its variant for tiles that straddle images (72 KB)
+__device__ const u32x4 kZeroBlock[128] = {};   // 2 KB of zeros: a halo slot outside the image walks through it chunk by chunk
+
+template <typename F, int... S>
+__device__ __forceinline__ void for_each_step(F &&f, std::integer_sequence<int, S...>)
+{
+    (f(std::integral_constant<int, S>{}), ...);
+}
+
+template <int WM, int WN, int SA>
+__global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_wreg_kernel(ConvArgs p)
+{
+    typedef bf16_t T;
+    constexpr int NW = WM * WN, NT = NW * 64, BM = WM * 128, BN = WN * 64, TM = 4, TN = 2;
+    constexpr int KC = 32;                       // channels per chunk (one 64-byte LDS row)
+    constexpr int NQ = (SA * 5 + NT - 1) / NT;   // halo copies per thread and chunk
+    constexpr int ABUF = NQ * NT * 16;           // bytes per halo buffer (>= SA * 80)
+    constexpr int R = 3, D = R - 1;              // ring of weight steps in registers, prefetch distance
+    constexpr int STEPS = 18;                    // (tap, k-group) steps per chunk
+    static_assert(STEPS % R == 0, "ring positions must repeat every chunk");
+
+    extern __shared__ __align__(16) char smem[];   // [2][ABUF]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wv % WM, wn = wv / WM;
+    const int r = lane & 31, khalf = lane >> 5;
+    // (XCD-aware numbering as in the kernel above)
+    const int nblk = gridDim.x, xcd = blockIdx.x & 7;
+    const int bid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + (blockIdx.x >> 3);
+    const int tile_n = bid % p.tiles_n, tile_m = bid / p.tiles_n;
+    const int n0 = tile_n * BN;
+    const TileOrigin org = tile_origin(p.g, tile_m);
+    const int pitch = p.g.pitch;
+    const int nchunks = p.CinP / KC;
+    const size_t xrow = (size_t)p.CinP * sizeof(T);
+
+    // source of each of this lane's halo slots (chunk 0)
+    const char *asrc[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int slot = (q * NW + wv) * 64 + lane;
+        const int row = slot / 5, seg = slot - row * 5;
+        const int px = (row < p.g.S && seg < 4) ? halo_pixel(p.g, org, row) : -1;
+        asrc[q] = px < 0 ? reinterpret_cast<const char *>(kZeroBlock) : p.x + (size_t)px * xrow + seg * 16;
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    auto copy_halo = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ABUF + (q * NW + wv) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[q]) : "m0", "memory");
+        }
+    };
+    auto next_chunk = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) asrc[q] += KC * sizeof(T);
+    };
+
+    // byte address (inside a buffer) of tap (0,0) of this lane's pixel rows, k-half included
+    int arow[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int m, hrow;
+        tile_row(p.g, org, wm * 128 + i * 32 + r, m, hrow);
+        arow[i] = hrow * kRowBytes + khalf * 16;
+    }
+
+    // weight fragment (tap t, k block kb, channels c..c+31): 1 KB at ((t*KB + kb)*Cout + c) * 32 bytes
+    const int KB = p.CinP / 16;
+    unsigned voff[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) voff[j] = (unsigned)min(n0 + wn * 64 + j * 32 + r, p.Cout - 1) * 32u + khalf * 16;   // channels past Cout are never stored
+    u32x4 bq[R][TN];
+    auto load_w = [&](int chunk, int t, int g, u32x4(&dst)[TN]) __attribute__((always_inline)) {
+        const char *sb = p.w + ((size_t)(t * KB + chunk * 2 + g) * p.Cout) * 32;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)sb);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uintptr_t)sb >> 32));
+        const unsigned long long sbase = ((unsigned long long)hi << 32) | lo;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst[j]) : "v"(voff[j]), "s"(sbase) : "memory");
+    };
+
+    f32x16 acc[TM][TN];
+    init_acc<BN, WN>(acc, p, n0, wn, khalf);
+
+    // prologue: the first two halo chunks and the first D weight steps
+    copy_halo(0);
+    if (nchunks > 1) { next_chunk(); copy_halo(1); }
+    for_each_step([&](auto ic) {
+        constexpr int s = decltype(ic)::value;
+        load_w(0, s / 2, s % 2, bq[s % R]);
+    }, std::make_integer_sequence<int, D>{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    spread_acc(acc);
+
+    u32x4 af[2][TM];
+    auto read_halo = [&](int buf, int t, int g, u32x4(&dst)[TM]) __attribute__((always_inline)) {
+        const int kh = t / 3, kw = t - kh * 3;
+        const char *base = smem + buf * ABUF + (kh * pitch + kw) * kRowBytes + g * 32;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) dst[i] = *reinterpret_cast<const u32x4 *>(base + arow[i]);
+    };
+    read_halo(0, 0, 0, af[0]);
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int ab = c & 1;
+        const int cn = min(c + 1, nchunks - 1);
+        for_each_step([&](auto ic) {
+            constexpr int s = decltype(ic)::value;
+            constexpr int sp = (s + D) % STEPS;   // step whose weights are requested now
+            if (s == STEPS - 1) {
+                // Every halo read of this chunk has been issued, and the next chunk's copies were issued a
+                // whole chunk ago (2 * STEPS weight loads since then).  After the barrier the other buffer is
+                // published and this one is free for the chunk after next.
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * STEPS) : "memory");
+                __builtin_amdgcn_s_barrier();
+                if (c + 2 < nchunks) next_chunk();   // (past the end: the last chunk again, never read; keeps the wait counts static)
+                copy_halo(ab);
+            }
+            load_w(s + D >= STEPS ? cn : c, sp / 2, sp % 2, bq[sp % R]);
+            if (s < STEPS - 1) read_halo(ab, (s + 1) / 2, (s + 1) % 2, af[(s + 1) & 1]);
+            else read_halo(ab ^ 1, 0, 0, af[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            // This step's two weight loads were issued D steps ago; since then came the loads of D more steps
+            // and, around the last step of a chunk, the NQ halo copies.
+            constexpr int younger = 2 * D + ((s == STEPS - 1 || s < D - 1) ? NQ : 0);
+            u32x4 b0 = bq[s % R][0], b1 = bq[s % R][1];
+            asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b0), "+v"(b1) : "n"(younger));
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, af[s & 1][i]);
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b0), a, acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b1), a, acc[i][1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }, std::make_integer_sequence<int, STEPS>{});
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the weight loads and halo copies issued past the end
+    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+}
+
+template <int WM, int WN, int SA>
+static int launch_conv_wreg(const ConvArgs &a0, const TileGeom &g, hipStream_t stream)
+{
+    ConvArgs a = a0;
+    constexpr int NT = WM * WN * 64, BN = WN * 64;
+    constexpr int NQ = (SA * 5 + NT - 1) / NT;
+    a.g = g;
+    a.tiles_n = (a.Cout + BN - 1) / BN;
+    a.rowsA = SA;
+    const size_t lds = (size_t)2 * NQ * NT * 16;   // (more than the epilogue's staging blocks)
+    auto kern = conv3x3_igemm_wreg_kernel<WM, WN, SA>;
+    if (!raise_lds_limit(reinterpret_cast<const void *>(kern))) return VGG_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n)), dim3(NT), lds, stream, a);
+    return launch_status();
+}
+
 template <typename T, int BM, int BN, int WM, int WN, int SA>
 static int launch_conv_dma(const ConvArgs &a0, const TileGeom &g, hipStream_t stream)
 {
@@ -662,7 +845,7 @@ __global__ __launch_bounds__(256) void conv_split_finish_kernel(const float *__r
 // Which kernel a shape gets, and whether its contraction is split over several workgroups per tile.
 struct ConvPlan {
     TileGeom g;
-    bool narrow, dma, dma_big, half;
+    bool narrow, dma, dma_big, half, wreg;
     int ksplit, kchunks;
 };
 
@@ -699,6 +882,10 @@ static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bo
         const TileGeom h = make_tile_geom(N, H, W, 128);
         if (h.S <= kDmaHaloRowsHalf) { c.g = h; c.half = true; }
     }
+    // bf16, 128-wide column tiles, whole contraction in one workgroup: the kernel that keeps the weights in
+    // registers (its 256-pixel tile and halo are those of the direct-to-LDS kernels, so dma / dma_big decide
+    // the halo size here as well)
+    c.wreg = dtype == VGG_BF16 && !c.narrow && (c.dma || c.dma_big) && c.ksplit == 1;
     return c;
 }
 
@@ -716,7 +903,7 @@ void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout,
 {
     const ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, pool);
     const int bn = c.narrow ? 64 : 128;
-    info[0] = c.half ? 3 : (c.dma ? 1 : (c.dma_big ? 2 : 0));
+    info[0] = c.wreg ? (c.dma ? 4 : 5) : (c.half ? 3 : (c.dma ? 1 : (c.dma_big ? 2 : 0)));
     info[1] = c.g.rows;
     info[2] = bn;
     info[3] = c.g.mode;
@@ -768,7 +955,9 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
             rc = narrow ? launch_conv<float, 256, 64, 4, 1>(a, N, H, W, stream)
                         : launch_conv<float, 256, 128, 4, 2>(a, N, H, W, stream);
     } else {
-        if (dma)
+        if (c.wreg && c.ksplit == 1)
+            rc = dma ? launch_conv_wreg<2, 2, kWregHaloRows>(a, g, stream) : launch_conv_wreg<2, 2, kWregHaloRowsBig>(a, g, stream);
+        else if (dma)
             rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)
                         : launch_conv_dma<bf16_t, 256, 128, 4, 2, kDmaHaloRows>(a, g, stream);
         else if (dma_big)

@@ -14,4 +14,16 @@ struct FlipJobs {
     int n;
 };
 
+// Arguments of the batched update of packed convolution weights with a bf16 working copy
+// (sgd_update_master_conv in pointwise.hip): tensor j is [9][Cout][CinP] fp32 at theta[j] (master) and
+// grad[j]; copy[j] is its bf16 copy in the layout the convolution kernels read.
+struct SgdConvJobs {
+    float *theta[kMaxFlipJobs];
+    const float *grad[kMaxFlipJobs];
+    unsigned short *copy[kMaxFlipJobs];
+    int Cout[kMaxFlipJobs], CinP[kMaxFlipJobs];
+    int first[kMaxFlipJobs + 1];   // first workgroup of each tensor (filled by the launcher)
+    int n;
+};
+
 }  // namespace vgg

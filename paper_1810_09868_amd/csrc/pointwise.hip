@@ -204,6 +204,42 @@ int sgd_update_master(size_t n, float *theta, const float *grad, float lr, void 
     return launch_status();
 }
 
+// The same for the convolution weights of a whole network in one launch: the fp32 master tensors are
+// [9][Cout][CinP] row-major (as are the gradients), the bf16 working copies have their columns blocked by
+// 16 (packed_w_index).  Workgroups [first[j], first[j+1]) serve tensor j, one thread per four columns.
+__global__ __launch_bounds__(256) void sgd_master_conv_kernel(SgdConvJobs J, float lr)
+{
+    int j = 0;
+    while (j + 1 < J.n && (int)blockIdx.x >= J.first[j + 1]) ++j;
+    const int Cout = J.Cout[j], CinP = J.CinP[j];
+    const size_t i = (size_t)((int)blockIdx.x - J.first[j]) * 256 + threadIdx.x;   // quad index
+    const size_t n4 = (size_t)9 * Cout * CinP / 4;
+    if (i >= n4) return;
+    f32x4 t = reinterpret_cast<f32x4 *>(J.theta[j])[i];
+    const f32x4 g = reinterpret_cast<const f32x4 *>(J.grad[j])[i];
+    t.x = sgd_step(t.x, g.x, lr); t.y = sgd_step(t.y, g.y, lr); t.z = sgd_step(t.z, g.z, lr); t.w = sgd_step(t.w, g.w, lr);
+    reinterpret_cast<f32x4 *>(J.theta[j])[i] = t;
+    const size_t e = i * 4;
+    const int col = (int)(e % CinP);
+    const size_t tr = e / CinP;
+    const int row = (int)(tr % Cout), tap = (int)(tr / Cout);
+    store4(J.copy[j] + packed_w_index<bf16_t>(tap, row, col, Cout, CinP), t.x, t.y, t.z, t.w);
+}
+
+int sgd_update_master_conv(SgdConvJobs &jobs, float lr, hipStream_t s)
+{
+    if (jobs.n < 1 || jobs.n > kMaxFlipJobs) return VGG_ERR_UNSUPPORTED;
+    int total = 0;
+    for (int j = 0; j < jobs.n; ++j) {
+        if (jobs.CinP[j] % 4) return VGG_ERR_UNSUPPORTED;
+        jobs.first[j] = total;
+        total += (int)(((size_t)9 * jobs.Cout[j] * jobs.CinP[j] / 4 + 255) / 256);
+    }
+    jobs.first[jobs.n] = total;
+    hipLaunchKernelGGL(sgd_master_conv_kernel, dim3((unsigned)total), dim3(256), 0, s, jobs, lr);
+    return launch_status();
+}
+
 // ------------------------------------------------------- layout transforms
 // NCHW fp32 -> NHWC T with zero padding of the channels up to Cpad.  One
 // thread per output pixel; reads are coalesced along w for each channel.
@@ -307,8 +343,9 @@ int convert(int sd, int dd, size_t n, const void *src, void *dst, hipStream_t s)
 }
 
 // ---------------------------------------------------------- weight packing
-// forward:  dst[(t*Cout + co)*CinP + ci]  = w[co][ci][t]          (zeros for ci >= Cin)
-// flipped:  dst[(t*Cin + ci)*CoutP + co]  = w[co][ci][8 - t]      (zeros for co >= Cout)
+// forward:  element (t, co, ci) of a [Cout][CinP] operand  = w[co][ci][t]          (zeros for ci >= Cin)
+// flipped:  element (t, ci, co) of a [Cin][CoutP] operand  = w[co][ci][8 - t]      (zeros for co >= Cout)
+// at the position packed_w_index<T> gives (fp32: row-major; bf16: columns blocked by 16).
 template <typename T>
 __global__ void pack_conv_w_kernel(const float *__restrict__ w, T *__restrict__ dst, int Cin, int Cout, int rows,
                                    int colsP, int flip)
@@ -325,7 +362,7 @@ __global__ void pack_conv_w_kernel(const float *__restrict__ w, T *__restrict__ 
     } else {
         if (c < Cout) v = w[((size_t)c * Cin + rr) * 9 + (8 - t)];
     }
-    Elem<T>::store(dst + idx, v);
+    Elem<T>::store(dst + packed_w_index<T>(t, rr, c, rows, colsP), v);
 }
 
 // colsP: padded length of the contiguous dimension (0: the granularity of dtype)
@@ -362,7 +399,7 @@ __global__ __launch_bounds__(256) void flip_packed_w_kernel(const float *__restr
 #pragma unroll
     for (int r = ty; r < 32; r += 8) {
         const int ci = ci0 + r, co = co0 + tx;
-        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + ((size_t)t * CinP + ci) * CoutP + co, tile[tx][r]);
+        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + packed_w_index<TD>(t, ci, co, CinP, CoutP), tile[tx][r]);
     }
 }
 
@@ -401,7 +438,7 @@ __global__ __launch_bounds__(256) void flip_packed_w_all_kernel(FlipJobs J)
 #pragma unroll
     for (int r = ty; r < 32; r += 8) {
         const int ci = ci0 + r, co = co0 + tx;
-        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + ((size_t)t * CinP + ci) * CoutP + co, tile[tx][r]);
+        if (ci < CinP && co < CoutP) Elem<TD>::store(dst + packed_w_index<TD>(t, ci, co, CinP, CoutP), tile[tx][r]);
     }
 }
 
