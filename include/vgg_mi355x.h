@@ -330,7 +330,8 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
  *   [0] kernel: 0 register-staged implicit GEMM, 1 / 2 / 3 direct-to-LDS
  *       implicit GEMM with room for 384 / 448 / 192 halo rows, 4 / 5 the
  *       bf16 implicit GEMM with its weights in registers and room for
- *       384 / 448 halo rows; weight
+ *       384 / 448 halo rows, 6 / 7 the same with 320-pixel tiles and one
+ *       workgroup per compute unit; weight
  *       gradient: 100 linear tiles, 114 / 116 patches 14 / 16 pixels wide,
  *       103 the kernel for at most three input channels (fp32); 116 / 117
  *       the bf16 kernel and its variant for at most 32 input channels

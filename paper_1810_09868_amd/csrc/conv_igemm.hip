@@ -615,9 +615,11 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
 // removes the weights from LDS traffic (half the fragment reads), the per-stage weight copies and
 // their barrier: one barrier per 32-channel chunk, i.e. per 144 MFMAs of a wave.
 //
-// Workgroup: WM x WN waves, each a 128-pixel x 64-channel sub-tile (4 x 2 MFMA blocks, 128
-// accumulator registers), two workgroups per CU.  A chunk is 18 steps (tap, k-group); a step is 4
-// halo-fragment reads and 8 MFMAs.  The halo of a chunk is copied by global_load_lds_dwordx4 into one
+// Workgroup: WM x WN waves, each a (32 TM)-pixel x 64-channel sub-tile: TM = 4 (4 x 2 MFMA blocks, 128
+// accumulator registers) with two workgroups per CU, or TM = 5 with one workgroup per CU and twice the
+// registers per wave, for launches whose 256-pixel tiles would number between one and two per CU (then
+// the CUs with two need twice as long as those with one: 320-pixel tiles give every CU at most one).
+// A chunk is 18 steps (tap, k-group); a step is TM halo-fragment reads and 2 TM MFMAs.  The halo of a chunk is copied by global_load_lds_dwordx4 into one
 // of two buffers a whole chunk ahead; rows are 80 bytes (64 data + 16 pad, conflict-free fragment
 // reads at addresses that are a per-lane base plus an offset per tap); the copy treats a buffer as
 // consecutive 16-byte slots, slot s = row s / 5, segment s % 5, every lane supplying the source
@@ -637,15 +639,15 @@ __device__ __forceinline__ void for_each_step(F &&f, std::integer_sequence<int, 
     (f(std::integral_constant<int, S>{}), ...);
 }
 
-template <int WM, int WN, int SA>
-__global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_wreg_kernel(ConvArgs p)
+template <int WM, int WN, int SA, int TM, int OCC>
+__global__ __launch_bounds__(WM *WN * 64, OCC) void conv3x3_igemm_wreg_kernel(ConvArgs p)
 {
     typedef bf16_t T;
-    constexpr int NW = WM * WN, NT = NW * 64, BM = WM * 128, BN = WN * 64, TM = 4, TN = 2;
+    constexpr int NW = WM * WN, NT = NW * 64, BM = WM * TM * 32, BN = WN * 64, TN = 2;
     constexpr int KC = 32;                       // channels per chunk (one 64-byte LDS row)
     constexpr int NQ = (SA * 5 + NT - 1) / NT;   // halo copies per thread and chunk
     constexpr int ABUF = NQ * NT * 16;           // bytes per halo buffer (>= SA * 80)
-    constexpr int R = 3, D = R - 1;              // ring of weight steps in registers, prefetch distance
+    constexpr int R = 6, D = R - 1;              // ring of weight steps in registers, prefetch distance
     constexpr int STEPS = 18;                    // (tap, k-group) steps per chunk
     static_assert(STEPS % R == 0, "ring positions must repeat every chunk");
 
@@ -681,6 +683,15 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_wreg_kernel(Conv
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[q]) : "m0", "memory");
         }
     };
+    // the copies of one chunk in 2 TM parts (one after each MFMA of a step)
+    auto copy_halo_part = [&](int buf, int part) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            if (q * (2 * TM) / NQ != part) continue;
+            const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ABUF + (q * NW + wv) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[q]) : "m0", "memory");
+        }
+    };
     auto next_chunk = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < NQ; ++q) asrc[q] += KC * sizeof(T);
@@ -691,7 +702,7 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_wreg_kernel(Conv
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         int m, hrow;
-        tile_row(p.g, org, wm * 128 + i * 32 + r, m, hrow);
+        tile_row(p.g, org, wm * (TM * 32) + i * 32 + r, m, hrow);
         arow[i] = hrow * kRowBytes + khalf * 16;
     }
 
@@ -734,44 +745,69 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void conv3x3_igemm_wreg_kernel(Conv
     };
     read_halo(0, 0, 0, af[0]);
 
+    // Instruction order inside a step: a wave issues in order and an MFMA holds the matrix pipe for 32
+    // cycles, so every other instruction of a step (the four halo-fragment reads of the next step, the two
+    // weight loads of step s + D) is issued right after an MFMA, in its shadow; issued as a block before
+    // the MFMAs they would leave the pipe idle whenever the SIMD's other wave is not multiplying.
+    // The weight fragments are requested in the order (chunk, tap, k-group); the scalar pointer to the
+    // next one moves by one of three constants (next k-group, next tap, next chunk), so a step spends two
+    // scalar additions on it.
+    const long long w_g = (long long)p.Cout * 32;                     // next k-group of the same tap
+    const long long w_t = (long long)KB * p.Cout * 32 - w_g;          // k-group 1 -> k-group 0 of the next tap
+    const long long w_c = 2 * w_g - 8 * (w_t + w_g) - w_g;            // last tap, k-group 1 -> first tap of the next chunk
+    const long long w_same = w_c - 2 * w_g;                           // ... of the same chunk again (past the end)
+    const char *wnext = p.w + (size_t)((D / 2) * KB + D % 2) * p.Cout * 32;   // step D of chunk 0 (D < 18)
     for (int c = 0; c < nchunks; ++c) {
         const int ab = c & 1;
-        const int cn = min(c + 1, nchunks - 1);
+        const long long w_wrap = c + 1 < nchunks ? w_c : w_same;
         for_each_step([&](auto ic) {
             constexpr int s = decltype(ic)::value;
-            constexpr int sp = (s + D) % STEPS;   // step whose weights are requested now
-            if (s == STEPS - 1) {
-                // Every halo read of this chunk has been issued, and the next chunk's copies were issued a
-                // whole chunk ago (2 * STEPS weight loads since then).  After the barrier the other buffer is
-                // published and this one is free for the chunk after next.
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(2 * STEPS) : "memory");
-                __builtin_amdgcn_s_barrier();
-                if (c + 2 < nchunks) next_chunk();   // (past the end: the last chunk again, never read; keeps the wait counts static)
-                copy_halo(ab);
-            }
-            load_w(s + D >= STEPS ? cn : c, sp / 2, sp % 2, bq[sp % R]);
-            if (s < STEPS - 1) read_halo(ab, (s + 1) / 2, (s + 1) % 2, af[(s + 1) & 1]);
-            else read_halo(ab ^ 1, 0, 0, af[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            // This step's two weight loads were issued D steps ago; since then came the loads of D more steps
-            // and, around the last step of a chunk, the NQ halo copies.
-            constexpr int younger = 2 * D + ((s == STEPS - 1 || s < D - 1) ? NQ : 0);
+            constexpr int sp = (s + D) % STEPS;   // step whose weights are requested during this one
+            // This step's two weight loads were issued during step s - D; since then came the loads of D - 1
+            // more steps and, when the last step of a chunk lies in between, its NQ halo copies (when it is
+            // step s - D itself: the copies issued after that step's second weight load, parts 4 and up).
+            constexpr int late_copies = NQ - ((4 * NQ + 2 * TM - 1) / (2 * TM));
+            constexpr int younger = 2 * (D - 1) + (s < D - 1 ? NQ : (s == D - 1 ? late_copies : 0));
             u32x4 b0 = bq[s % R][0], b1 = bq[s % R][1];
             asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b0), "+v"(b1) : "n"(younger));
+            if (s == STEPS - 1) {
+                // Every halo read of this chunk has been issued (the last ones during the previous step), and
+                // the wait above has also covered the next chunk's copies, issued a whole chunk ago.  After
+                // the barrier the other buffer is published and this one is free for the chunk after next.
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (c + 2 < nchunks) next_chunk();   // (past the end: the last chunk again, never read; keeps the wait counts static)
+            }
+            const int nbuf = s < STEPS - 1 ? ab : ab ^ 1;
+            constexpr int nt = ((s + 1) % STEPS) / 2, ng = (s + 1) % 2;
+            const char *abase = smem + nbuf * ABUF + ((nt / 3) * pitch + nt % 3) * kRowBytes + ng * 32;
+            const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)wnext);
+            const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uintptr_t)wnext >> 32));
+            const unsigned long long sbase = ((unsigned long long)hi << 32) | lo;
+            wnext += sp == STEPS - 1 ? w_wrap : (sp % 2 == 0 ? w_g : w_t);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const bf16x8 a = __builtin_bit_cast(bf16x8, af[s & 1][i]);
                 acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b0), a, acc[i][0], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                af[(s + 1) & 1][i] = *reinterpret_cast<const u32x4 *>(abase + arow[i]);
+                if (s == STEPS - 1) copy_halo_part(ab, 2 * i);       // (the copies into the freed buffer, spread over this step's MFMAs)
+                __builtin_amdgcn_sched_barrier(0);
                 acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b1), a, acc[i][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s == STEPS - 1) copy_halo_part(ab, 2 * i + 1);
+                if (i < TN)
+                    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[sp % R][i]) : "v"(voff[i]), "s"(sbase) : "memory");
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }, std::make_integer_sequence<int, STEPS>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the weight loads and halo copies issued past the end
     conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
 }
 
-template <int WM, int WN, int SA>
+template <int WM, int WN, int SA, int TM = 4, int OCC = 2>
 static int launch_conv_wreg(const ConvArgs &a0, const TileGeom &g, hipStream_t stream)
 {
     ConvArgs a = a0;
@@ -781,7 +817,7 @@ static int launch_conv_wreg(const ConvArgs &a0, const TileGeom &g, hipStream_t s
     a.tiles_n = (a.Cout + BN - 1) / BN;
     a.rowsA = SA;
     const size_t lds = (size_t)2 * NQ * NT * 16;   // (more than the epilogue's staging blocks)
-    auto kern = conv3x3_igemm_wreg_kernel<WM, WN, SA>;
+    auto kern = conv3x3_igemm_wreg_kernel<WM, WN, SA, TM, OCC>;
     if (!raise_lds_limit(reinterpret_cast<const void *>(kern))) return VGG_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.g.ntiles * a.tiles_n)), dim3(NT), lds, stream, a);
     return launch_status();
@@ -845,7 +881,7 @@ __global__ __launch_bounds__(256) void conv_split_finish_kernel(const float *__r
 // Which kernel a shape gets, and whether its contraction is split over several workgroups per tile.
 struct ConvPlan {
     TileGeom g;
-    bool narrow, dma, dma_big, half, wreg;
+    bool narrow, dma, dma_big, half, wreg, tall;
     int ksplit, kchunks;
 };
 
@@ -886,6 +922,21 @@ static ConvPlan conv_plan(int dtype, int N, int H, int W, int CinP, int Cout, bo
     // registers (its 256-pixel tile and halo are those of the direct-to-LDS kernels, so dma / dma_big decide
     // the halo size here as well)
     c.wreg = dtype == VGG_BF16 && !c.narrow && (c.dma || c.dma_big) && c.ksplit == 1;
+    // bf16, a launch that 256-pixel tiles cannot spread evenly (the 14x14 layers at batch 100: 308 tiles of 128
+    // channels, so some CUs would get two workgroups and the rest one): 320-pixel tiles, five pixel blocks per
+    // wave and one workgroup per CU with all its registers, when that gives every CU at most one tile.
+    c.tall = false;
+    if (dtype == VGG_BF16 && Cout > 64 && !pool && c.ksplit == 1 && c.g.ntiles * ((Cout + 127) / 128) < 512) {
+        const TileGeom t = make_tile_geom(N, H, W, 320);
+        const int tiles = t.ntiles * ((Cout + 127) / 128);
+        if (t.S <= kWregHaloRowsBig && tiles > 128 && tiles <= 256) {
+            c.g = t;
+            c.tall = c.wreg = true;
+            c.narrow = c.half = false;
+            c.dma = t.S <= kWregHaloRows;
+            c.dma_big = !c.dma;
+        }
+    }
     return c;
 }
 
@@ -903,7 +954,7 @@ void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout,
 {
     const ConvPlan c = conv_plan(dtype, N, H, W, CinP, Cout, pool);
     const int bn = c.narrow ? 64 : 128;
-    info[0] = c.wreg ? (c.dma ? 4 : 5) : (c.half ? 3 : (c.dma ? 1 : (c.dma_big ? 2 : 0)));
+    info[0] = c.wreg ? (c.dma ? 4 : 5) + (c.tall ? 2 : 0) : (c.half ? 3 : (c.dma ? 1 : (c.dma_big ? 2 : 0)));
     info[1] = c.g.rows;
     info[2] = bn;
     info[3] = c.g.mode;
@@ -955,7 +1006,10 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
             rc = narrow ? launch_conv<float, 256, 64, 4, 1>(a, N, H, W, stream)
                         : launch_conv<float, 256, 128, 4, 2>(a, N, H, W, stream);
     } else {
-        if (c.wreg && c.ksplit == 1)
+        // (weights in registers)
+        if (c.tall)
+            rc = dma ? launch_conv_wreg<2, 2, kWregHaloRows, 5, 1>(a, g, stream) : launch_conv_wreg<2, 2, kWregHaloRowsBig, 5, 1>(a, g, stream);
+        else if (c.wreg && c.ksplit == 1)
             rc = dma ? launch_conv_wreg<2, 2, kWregHaloRows>(a, g, stream) : launch_conv_wreg<2, 2, kWregHaloRowsBig>(a, g, stream);
         else if (dma)
             rc = narrow ? launch_conv_dma<bf16_t, 256, 64, 4, 1, kDmaHaloRows>(a, g, stream)

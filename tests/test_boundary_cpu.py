@@ -170,14 +170,17 @@ def test_convolution_plan_query():
     assert L.vgg_conv3x3_plan(0, 0, 1, 4, 4, 16, 16, buf, 3) == -2
     assert L.vgg_conv3x3_plan(0, 4, 1, 4, 4, 16, 16, buf, 7) == -3
     assert L.vgg_conv3x3_plan(B.PLAN_FWD_POOL, 0, 1, 14, 14, 16, 16, buf, 7) == -7     # pool fusion needs 16-pixel patches
-    # batch 100: 256-pixel tiles, contraction never split; the 14x14 layers take 64-wide column tiles (fp32: 128 pixels)
+    # batch 100: 256-pixel tiles, contraction never split; the 14x14 layers take 128-pixel tiles with 64-wide column
+    # tiles (fp32) or 320-pixel tiles, one per compute unit (bf16)
     for dtype in (B.F32, B.BF16):
         for (h, ci, co) in ((224, 64, 64), (112, 128, 128), (56, 256, 256), (28, 512, 512), (14, 512, 512)):
             for op in (B.PLAN_FWD, B.PLAN_BWD_DATA):
                 info = B.vgg_conv3x3_plan(op, dtype, 100, h, h, ci, co)
                 assert info[5] == 1
-                assert info[1] == (128 if (dtype == B.F32 and h == 14) else 256)
-                assert info[2] == (64 if (co == 64 or h == 14) else 128)
+                assert info[1] == ((128 if dtype == B.F32 else 320) if h == 14 else 256)
+                assert info[2] == (64 if (co == 64 or (h == 14 and dtype == B.F32)) else 128)
+                if dtype == B.BF16 and h == 14:
+                    assert info[0] in (6, 7) and info[6] <= 256
                 assert info[1] * info[4] >= 100 * h * h
     # a single image: the last stages split their contraction over several workgroups
     assert B.vgg_conv3x3_plan(B.PLAN_FWD, B.BF16, 1, 14, 14, 512, 512)[5] > 1

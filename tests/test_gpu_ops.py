@@ -146,6 +146,82 @@ def test_conv3x3_bwd_data(dtype, shape):
     assert max_rel_err(from_nhwc(dx), ref * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
 
 
+# The convolution layers of the batch-100 benchmark whose launches take kernels that the small shapes above
+# never reach (bf16: weights in registers, with 256- and with 320-pixel tiles).  (N, H, W, Cin, Cout,
+# expected kernel of the forward call, expected kernel of the data gradient with a mask.)
+FULL_SIZE_LAYERS = [
+    (100, 112, 112, 64, 128, 4, 1),
+    (100, 56, 56, 128, 256, 5, 5),
+    (100, 56, 56, 256, 256, 5, 5),
+    (100, 28, 28, 256, 512, 4, 4),
+    (100, 28, 28, 512, 512, 4, 4),
+    (100, 14, 14, 512, 512, 7, 7),
+]
+
+
+def _sample_pixels(N, H, W, tile_rows, count, seed):
+    """Pixels (n, h, w) to check at full size: the tensor's first and last pixels, the corners of an image,
+    both sides of the first, a middle and the last tile boundary, and `count` random ones."""
+    M = N * H * W
+    flat = {0, 1, W - 1, W, H * W - 1, H * W, M - 1, M - W, M - H * W}
+    for t in (1, (M // tile_rows) // 2, M // tile_rows):
+        for d in (-1, 0, 1):
+            flat.add(min(max(t * tile_rows + d, 0), M - 1))
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    flat.update(int(v) for v in rng.integers(0, M, size=count))
+    flat = np.array(sorted(flat))
+    return flat // (H * W), (flat % (H * W)) // W, flat % W
+
+
+def _patches(t_nchw, n, h, w):
+    """The zero-padded 3x3 neighbourhoods [S, C, 3, 3] of the pixels (n[i], h[i], w[i])."""
+    _, C, H, W = t_nchw.shape
+    out = np.zeros((len(n), C, 3, 3), dtype=np.float64)
+    for dh in range(3):
+        for dw in range(3):
+            hh, ww = h + dh - 1, w + dw - 1
+            ok = (hh >= 0) & (hh < H) & (ww >= 0) & (ww < W)
+            out[ok, :, dh, dw] = t_nchw[n[ok], :, hh[ok], ww[ok]]
+    return out
+
+
+@pytest.mark.parametrize("shape", FULL_SIZE_LAYERS)
+def test_conv3x3_bf16_full_size_on_sampled_pixels(shape):
+    """Forward and data gradient at the benchmark's sizes, in the launch configuration it times; the oracle
+    computes the sampled pixels one neighbourhood at a time (all channels of each)."""
+    N, H, W, Cin, Cout, kernel_fwd, kernel_bwd = shape
+    dtype = B.BF16
+    plan = B.vgg_conv3x3_plan(B.PLAN_FWD, dtype, N, H, W, Cin, Cout)
+    assert plan[0] == kernel_fwd, plan
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_DATA, dtype, N, H, W, Cin, Cout)[0] == kernel_bwd
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape[:5]))
+    n, h, w = _sample_pixels(N, H, W, plan[1], 400, seed=H + Cin)
+    x = to_nhwc(d["x"], dtype)
+    # forward (bias, ReLU): the centre of the oracle's output over each 3x3 neighbourhood
+    y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), y, 1, ws)
+    torch.cuda.synchronize()
+    ref = R.conv3x3_fwd(_patches(d["x"], n, h, w), d["w"], d["b"], relu=True)[:, :, 1, 1]
+    got = y[torch.from_numpy(n).cuda(), torch.from_numpy(h).cuda(), torch.from_numpy(w).cuda()].float().cpu().numpy()
+    assert max_rel_err(got, ref) <= TOL[dtype]
+    del y
+    # data gradient, without and with the (x > 0) factor of the layer below
+    g = to_nhwc(d["dy"], dtype)
+    dx = torch.empty((N, H, W, Cin), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    wtf = _pack(dtype, d["w"], flip=1)
+    ref = R.conv3x3_bwd_data(_patches(d["dy"], n, h, w), d["w"])[:, :, 1, 1]
+    idx = (torch.from_numpy(n).cuda(), torch.from_numpy(h).cuda(), torch.from_numpy(w).cuda())
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, None, dx, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(dx[idx].float().cpu().numpy(), ref) <= TOL[dtype]
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, x, dx, ws)
+    torch.cuda.synchronize()
+    keep = x[idx].float().cpu().numpy() > 0
+    assert max_rel_err(dx[idx].float().cpu().numpy(), ref * keep) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
 def test_conv3x3_bwd_weight(dtype, shape):
