@@ -99,6 +99,16 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
     wide_ms = sum(conv_ms[l] for l in wide) / len(wide)                # average launch duration
     achieved = wide_flops / (wide_ms * 1e-3) / 1e12
     peak = PEAK_TFLOPS[dtype_name]
+    # The bf16 forward pass runs the first two convolutions and the first pool as one launch: the plan still
+    # lists the second convolution, with no launch behind it (its interval is the gap between two events).
+    fused01 = conv_ms[1] < 0.02 * conv_ms[0]
+    per_layer = []
+    for l in range(16):
+        if fused01 and l == 1:
+            per_layer.append({"layer": 1, "ms": 0.0, "tflops": None, "note": "in the launch of layer 0"})
+            continue
+        fl = conv_flops(N, l) + (conv_flops(N, 1) if fused01 and l == 0 else 0.0)
+        per_layer.append({"layer": l, "ms": round(conv_ms[l], 4), "tflops": round(fl / (conv_ms[l] * 1e-3) / 1e12, 1)})
     res = {
         "ms_per_step": dt * 1e3,
         "images_per_s": N / dt,
@@ -106,9 +116,9 @@ def run_forward_bench(dtype_name, N, steps, warmup, inp):
         "conv_tflops": total_conv_flops / (total_conv_ms * 1e-3) / 1e12,
         "pct_mfma_peak_conv": 100.0 * total_conv_flops / (total_conv_ms * 1e-3) / 1e12 / peak,
         "other_ms_per_step": other_ms,
-        "per_layer": [{"layer": l, "ms": round(conv_ms[l], 4),
-                       "tflops": round(conv_flops(N, l) / (conv_ms[l] * 1e-3) / 1e12, 1)} for l in range(16)],
-        "roofline": {"bound": "mfma", "kernel": "conv3x3_igemm_dma_kernel<%s,256,128,4,2,*>" % ("bf16" if dtype_name == "bf16" else "float"),
+        "per_layer": per_layer,
+        "roofline": {"bound": "mfma", "kernel": ("conv3x3_igemm_wreg_kernel<2,2,*,4,2>" if dtype_name == "bf16"
+                                                  else "conv3x3_igemm_dma_kernel<float,256,128,4,2,*>"),
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "launches_per_step": len(wide), "avg_launch_ms": wide_ms,
                      "traffic": recorded_traffic(dtype_name, N)},

@@ -169,6 +169,27 @@ int vgg_conv3x3_fwd_pool(int dtype, int N, int H, int W, int Cin, int Cout, cons
 int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, const void *w_packed,
                           const float *bias, void *y_nhwc, int relu, void *stream);
 
+/* The network's first two convolutions and first pool as one call
+ * (appendix table, forward column: the first two "convolution" rows and the
+ * first "reduce-window"; section on XLA: fused operations keep their
+ * intermediates on chip):
+ *   y2 = relu(conv3x3(relu(conv3x3(x, w1) + bias1), w2) + bias2),
+ *   pooled = maxpool2x2(y2),
+ * each convolution and the pool as defined for vgg_conv3x3_fwd /
+ * vgg_maxpool2x2, the first layer's output rounded to `dtype` before it
+ * enters the second, as when the two are called one after the other (the
+ * first layer adds its 27 products in another order than
+ * vgg_conv3x3_fwd_first, so a few values differ from that sequence by a
+ * rounding step).  x is the NCHW fp32 batch [N][3][H][W]; w1 / w2
+ * are the forward packings for 3 -> 64 and 64 -> 64 channels; y2
+ * [N][H][W][64] and pooled [N][H/2][W/2][64] are NHWC in `dtype`, either may
+ * be NULL (not both) and is then never written; no pooling positions are
+ * produced.  The first layer's output is not written at all.  bf16 only, H a
+ * multiple of 16 and W of 32 (VGG_ERR_UNSUPPORTED otherwise). */
+int vgg_conv3x3_fwd_first_pair(int dtype, int N, int H, int W, const float *x_nchw, const void *w1_packed,
+                               const float *bias1, const void *w2_packed, const float *bias2, void *y2_nhwc_or_null,
+                               void *pooled_nhwc_or_null, void *stream);
+
 /* dx[n,h,w,ci] = sum_{kh,kw,co} g[n,h-kh+1,w-kw+1,co] * w[co,ci,kh,kw]
  * (gradient with respect to the convolution's input; g is the gradient with
  * respect to its pre-activation output, zero outside the image).  w_tf is

@@ -20,7 +20,7 @@ NUM_CONV, NUM_FC = 16, 3
 EXPORTS = [
     "vgg_strerror", "vgg_padded_channels", "vgg_conv_pack_weights", "vgg_conv_unpack_weights",
     "vgg_nchw_to_nhwc", "vgg_nhwc_to_nchw", "vgg_convert",
-    "vgg_conv3x3_fwd_workspace_bytes", "vgg_conv3x3_fwd", "vgg_conv3x3_fwd_pool", "vgg_conv3x3_fwd_first",
+    "vgg_conv3x3_fwd_workspace_bytes", "vgg_conv3x3_fwd", "vgg_conv3x3_fwd_pool", "vgg_conv3x3_fwd_first", "vgg_conv3x3_fwd_first_pair",
     "vgg_conv3x3_bwd_data_workspace_bytes", "vgg_conv3x3_bwd_data",
     "vgg_conv3x3_bwd_weight_workspace_bytes", "vgg_conv3x3_bwd_weight",
     "vgg_maxpool2x2", "vgg_maxpool2x2_bwd",
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         L.vgg_conv3x3_fwd.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
         L.vgg_conv3x3_fwd_pool.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _sz, _vp]
         L.vgg_conv3x3_fwd_first.argtypes = [_i] * 4 + [_vp, _vp, _vp, _vp, _i, _vp]
+        L.vgg_conv3x3_fwd_first_pair.argtypes = [_i] * 4 + [_vp] * 8
         L.vgg_conv3x3_bwd_data.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.vgg_conv3x3_bwd_weight.argtypes = [_i] * 6 + [_vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.vgg_maxpool2x2.argtypes = [_i] * 5 + [_vp, _vp, _vp, _vp]
@@ -191,6 +192,11 @@ def vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, w_packed, bias, y, pooled
 def vgg_conv3x3_fwd_first(dtype, N, H, W, x_nchw, w_packed, bias, y, relu):
     _chk(lib().vgg_conv3x3_fwd_first(dtype, N, H, W, _ptr(x_nchw), _ptr(w_packed), _ptr(bias), _ptr(y), int(relu),
                                      _stream()), "vgg_conv3x3_fwd_first")
+
+
+def vgg_conv3x3_fwd_first_pair(dtype, N, H, W, x_nchw, w1_packed, bias1, w2_packed, bias2, y2, pooled):
+    _chk(lib().vgg_conv3x3_fwd_first_pair(dtype, N, H, W, _ptr(x_nchw), _ptr(w1_packed), _ptr(bias1), _ptr(w2_packed),
+                                          _ptr(bias2), _ptr(y2), _ptr(pooled), _stream()), "vgg_conv3x3_fwd_first_pair")
 
 
 def vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout) -> int:

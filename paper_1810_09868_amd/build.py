@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["conv_igemm.hip", "conv_first.hip", "conv_wgrad.hip", "conv_wgrad_bf16.hip", "pointwise.hip", "fc.hip", "probe.hip", "api.hip"]
+SOURCES = ["conv_igemm.hip", "conv_first.hip", "conv_pair.hip", "conv_wgrad.hip", "conv_wgrad_bf16.hip", "pointwise.hip", "fc.hip", "probe.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-inline-asm"]
 LIB = os.path.join(HERE, "libvgg_mi355x.so")

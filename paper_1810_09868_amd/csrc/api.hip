@@ -27,6 +27,9 @@ int conv3x3_igemm(int dtype, int N, int H, int W, int CinP, int Cout, const void
                   const void *mask, void *y, void *pool, unsigned char *argmax, int relu, void *part_ws, hipStream_t stream);
 size_t conv3x3_igemm_workspace(int dtype, int N, int H, int W, int CinP, int Cout);
 bool conv3x3_pool_fusable(int dtype, int H, int W, int Cout);
+bool conv_first_pair_ok(int dtype, int H, int W);
+int conv_first_pair(int N, int H, int W, int CinP1, const float *x, const void *w1, const float *b1, const void *w2,
+                    const float *b2, void *y, void *pool, hipStream_t stream);
 int conv_first(int dtype, int N, int H, int W, int CinP, const float *x, const void *w, const float *bias, void *y,
                int relu, hipStream_t stream);
 void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout, bool pool, int info[7]);
@@ -260,7 +263,19 @@ void run_forward(const vgg_config *c, const PackedLayout &P, const WsLayout &L, 
     // of the images, which the first layer's weight gradient reads.
     if (training) VGG_STEP(rec, K_OTHER, nchw_to_nhwc(dt, N, 3, c->H, c->W, x0_channels(dt, P.cinp[0]), x, ws + L.x0, s));
     const char *cur = ws + L.x0;
-    for (int l = 0; l < VGG19_NUM_CONV; ++l) {
+    // Forward only, bf16, patch-tiled image sizes: the first two convolutions and the first pool run as one
+    // kernel and the 64-channel full-resolution activations between and after them are never written (the
+    // backward pass would need them, so the training step keeps the separate launches).
+    const bool pair = !training && conv_first_pair_ok(dt, c->H, c->W);
+    if (pair) {
+        VGG_STEP(rec, K_CONV, conv_first_pair(N, c->H, c->W, P.cinp[0], x, pk + P.conv_w[0],
+                                             reinterpret_cast<const float *>(pk + P.conv_b[0]), pk + P.conv_w[1],
+                                             reinterpret_cast<const float *>(pk + P.conv_b[1]), nullptr, ws + L.pooled[1], s));
+        rec.skip(K_CONV);  // the second convolution and the pool: in the launch above; listed so that the plan
+        rec.skip(K_POOL);  // still shows sixteen convolutions and five pools
+        cur = ws + L.pooled[1];
+    }
+    for (int l = pair ? 2 : 0; l < VGG19_NUM_CONV; ++l) {
         char *out = ws + L.act[l];
         // On patch-tiled layers the 2x2 maximum (and, for training, its position) is taken in the
         // convolution's epilogue and the un-pooled tensor is never written: the backward pass needs
@@ -580,6 +595,20 @@ int vgg_conv3x3_fwd_first(int dtype, int N, int H, int W, const float *x_nchw, c
     if (!conv_shape_ok(N, H, W, 3, 64)) return VGG_ERR_SHAPE;
     if (!aligned16(x_nchw) || !aligned16(w) || !aligned16(y)) return VGG_ERR_ALIGN;
     return conv_first(dtype, N, H, W, padded_channels(dtype, 3), x_nchw, w, bias, y, relu ? 1 : 0, (hipStream_t)stream);
+}
+
+int vgg_conv3x3_fwd_first_pair(int dtype, int N, int H, int W, const float *x_nchw, const void *w1, const float *bias1,
+                               const void *w2, const float *bias2, void *y2_or_null, void *pooled_or_null, void *stream)
+{
+    if (!x_nchw || !w1 || !w2 || (!y2_or_null && !pooled_or_null)) return VGG_ERR_NULL;
+    if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
+    if (!conv_shape_ok(N, H, W, 3, 64)) return VGG_ERR_SHAPE;
+    if (!conv_first_pair_ok(dtype, H, W)) return VGG_ERR_UNSUPPORTED;
+    if (!aligned16(x_nchw) || !aligned16(w1) || !aligned16(w2) || !aligned16(y2_or_null) || !aligned16(pooled_or_null) ||
+        !aligned16(bias2))
+        return VGG_ERR_ALIGN;
+    return conv_first_pair(N, H, W, padded_channels(dtype, 3), x_nchw, w1, bias1, w2, bias2, y2_or_null, pooled_or_null,
+                           (hipStream_t)stream);
 }
 
 size_t vgg_conv3x3_bwd_data_workspace_bytes(int dtype, int N, int H, int W, int Cin, int Cout)

@@ -126,6 +126,66 @@ def test_conv3x3_fwd_first_layer_from_nchw(dtype, shape):
         assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("shape", [(1, 16, 32), (2, 32, 64), (3, 48, 32), (22, 64, 128)])
+def test_conv3x3_fwd_first_pair(shape):
+    """The first two convolutions and the first pool as one call: against the oracle's three operations and
+    against the library's separate calls (same products; the first layer adds its 27 in another order, so a
+    few values differ by a rounding step).  The pooled tensor must be exactly the 2x2 maximum of the
+    un-pooled one.  The last shape has 352 patches, more than the launch has workgroups."""
+    N, H, W = shape
+    dtype = B.BF16
+    d1 = synth.conv_layer_inputs(N, H, W, 3, 64, seed=sum(shape))
+    d2 = synth.conv_layer_inputs(1, 4, 4, 64, 64, seed=sum(shape) + 1)
+    x = np.abs(d1["x"])      # image-like: non-negative
+    b1 = np.linspace(-0.2, 0.3, 64).astype(np.float32)
+    b2 = np.linspace(0.1, -0.4, 64).astype(np.float32)
+    y1 = R.conv3x3_fwd(x, d1["w"], b1, relu=True)
+    y2 = R.conv3x3_fwd(y1, d2["w"], b2, relu=True)
+    pooled_ref, _ = R.maxpool2x2(y2)
+    w1, w2 = _pack(dtype, d1["w"]), _pack(dtype, d2["w"])
+    xd = dev(x.astype(np.float32))
+    y2_g = torch.empty((N, H, W, 64), dtype=TDT[dtype], device="cuda")
+    po_g = torch.empty((N, H // 2, W // 2, 64), dtype=TDT[dtype], device="cuda")
+    B.vgg_conv3x3_fwd_first_pair(dtype, N, H, W, xd, w1, dev(b1), w2, dev(b2), y2_g, po_g)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y2_g), y2) <= TOL[dtype]
+    assert max_rel_err(from_nhwc(po_g), pooled_ref) <= TOL[dtype]
+    # pooled == 2x2 maximum of the un-pooled output, bit for bit
+    po_chk = torch.empty_like(po_g)
+    B.vgg_maxpool2x2(dtype, N, H, W, 64, y2_g, po_chk)
+    torch.cuda.synchronize()
+    assert torch.equal(po_g.view(torch.int16), po_chk.view(torch.int16))
+    # the separate calls: bf16 roundings of slightly different fp32 sums
+    y1_s = torch.empty((N, H, W, 64), dtype=TDT[dtype], device="cuda")
+    y2_s = torch.empty_like(y2_g)
+    po_s = torch.empty_like(po_g)
+    B.vgg_conv3x3_fwd_first(dtype, N, H, W, xd, w1, dev(b1), y1_s, 1)
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, 64, 64))
+    B.vgg_conv3x3_fwd_pool(dtype, N, H, W, 64, 64, y1_s, w2, dev(b2), y2_s, po_s, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y2_g), from_nhwc(y2_s)) <= 2.0 ** -7
+    # only one of the two outputs
+    po_only = torch.zeros_like(po_g)
+    B.vgg_conv3x3_fwd_first_pair(dtype, N, H, W, xd, w1, dev(b1), w2, dev(b2), None, po_only)
+    torch.cuda.synchronize()
+    assert torch.equal(po_only.view(torch.int16), po_g.view(torch.int16))
+    y_only = torch.zeros_like(y2_g)
+    B.vgg_conv3x3_fwd_first_pair(dtype, N, H, W, xd, w1, dev(b1), w2, dev(b2), y_only, None)
+    torch.cuda.synchronize()
+    assert torch.equal(y_only.view(torch.int16), y2_g.view(torch.int16))
+
+
+def test_conv3x3_fwd_first_pair_rejects_other_shapes_and_dtypes():
+    x = torch.zeros((1, 3, 16, 16), device="cuda")
+    w = torch.zeros((9 * 64 * 64,), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((1, 16, 16, 64), dtype=torch.bfloat16, device="cuda")
+    L = B.lib()
+    args = (x.data_ptr(), w.data_ptr(), None, w.data_ptr(), None, y.data_ptr(), None, None)
+    assert L.vgg_conv3x3_fwd_first_pair(B.BF16, 1, 16, 16, *args) == -7      # W not a multiple of 32
+    assert L.vgg_conv3x3_fwd_first_pair(B.F32, 1, 16, 32, *args) == -7       # fp32
+    assert L.vgg_conv3x3_fwd_first_pair(B.BF16, 1, 16, 32, x.data_ptr(), w.data_ptr(), None, w.data_ptr(), None, None, None, None) == -1
+
+
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
 def test_conv3x3_bwd_data(dtype, shape):
