@@ -804,7 +804,48 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void conv3x3_igemm_wreg_kernel(Co
         }, std::make_integer_sequence<int, STEPS>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the weight loads and halo copies issued past the end
-    conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+    if (p.pool || p.mask || !p.y || (p.Cout & 7)) {
+        conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+        return;
+    }
+    // Plain store epilogue (no pool, no mask): straight from registers, without the trip through LDS and its
+    // barrier.  A lane holds four consecutive channels of a pixel per accumulator quarter; it swaps one quarter
+    // with its partner lane (same pixel, the other four channels of each group of eight: lane +- 32,
+    // v_permlane32_swap) and then owns eight consecutive channels, 16 bytes, of two quarters.
+    {
+        const float lo = p.relu ? 0.f : -__builtin_inff();
+        T *y = reinterpret_cast<T *>(p.y);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = tile_pixel(p.g, org, wm * (TM * 32) + i * 32 + r);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                unsigned x[4][2];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                    const f32x2_t v0 = {fmaxf(acc[i][j][a * 4], lo), fmaxf(acc[i][j][a * 4 + 1], lo)};
+                    const f32x2_t v1 = {fmaxf(acc[i][j][a * 4 + 2], lo), fmaxf(acc[i][j][a * 4 + 3], lo)};
+                    x[a][0] = __builtin_bit_cast(unsigned, __builtin_convertvector(v0, bf16x2_t));
+                    x[a][1] = __builtin_bit_cast(unsigned, __builtin_convertvector(v1, bf16x2_t));
+                }
+#pragma unroll
+                for (int ap = 0; ap < 2; ++ap) {
+                    // lanes 0-31 give their channels of quarter 2 ap + 1 and receive the partner's of quarter 2 ap
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(x[2 * ap][h], x[2 * ap + 1][h], false, false);
+                        x[2 * ap][h] = sw[0];
+                        x[2 * ap + 1][h] = sw[1];
+                    }
+                    const u32x4 v = {x[2 * ap][0], x[2 * ap][1], x[2 * ap + 1][0], x[2 * ap + 1][1]};
+                    const int col = n0 + wn * 64 + j * 32 + (2 * ap + khalf) * 8;
+                    if (m >= 0 && col < p.Cout) *reinterpret_cast<u32x4 *>(y + (size_t)m * p.Cout + col) = v;
+                }
+            }
+        }
+    }
 }
 
 template <int WM, int WN, int SA, int TM = 4, int OCC = 2>
