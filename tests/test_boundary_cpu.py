@@ -63,6 +63,15 @@ def test_argument_validation_happens_on_the_host():
     assert L.vgg_fc_static(0, 0, 8192, 4096, a, a, None, a, 0, 0, None) == -2
     assert L.vgg_fc_static(0, 4, 64, 8, a + 8, a, None, a, 0, 0, None) == -4
     assert B.vgg_fc_workspace_bytes(B.F32, 100, 25088, 4096) <= B.FC_STATIC_SCRATCH_BYTES
+    # the first two convolutions as one call: bf16 only, H % 16 == 0 and W % 32 == 0, at least one output
+    assert L.vgg_conv3x3_fwd_first_pair(1, 1, 16, 32, a, a, None, a, None, None, None, None) == -1
+    assert L.vgg_conv3x3_fwd_first_pair(1, 1, 16, 32, None, a, None, a, None, a, None, None) == -1
+    assert L.vgg_conv3x3_fwd_first_pair(7, 1, 16, 32, a, a, None, a, None, a, None, None) == -3
+    assert L.vgg_conv3x3_fwd_first_pair(1, 0, 16, 32, a, a, None, a, None, a, None, None) == -2
+    assert L.vgg_conv3x3_fwd_first_pair(0, 1, 16, 32, a, a, None, a, None, a, None, None) == -7
+    assert L.vgg_conv3x3_fwd_first_pair(1, 1, 16, 48, a, a, None, a, None, a, None, None) == -7
+    assert L.vgg_conv3x3_fwd_first_pair(1, 1, 24, 32, a, a, None, a, None, a, None, None) == -7
+    assert L.vgg_conv3x3_fwd_first_pair(1, 1, 16, 32, a, a + 2, None, a, None, a, None, None) == -4
     assert L.vgg_softmax(0, 10, a, a, None) == -2
     assert L.vgg_sgd_update(0, a, a, 0.1, None) == -2
     assert L.vgg_sgd_update(4, None, a, 0.1, None) == -1
@@ -109,6 +118,9 @@ def test_launch_plan_matches_paper_op_counts():
     assert fwd.count(1) == gold["convolution"][0] == 16
     assert fwd.count(4) == gold["reduce-window"][0] == 5
     assert fwd.count(6) == gold["dot"][0] == 3
+    # bf16 forward: the first two convolutions and the first pool are one launch, still listed as three steps
+    fwd16 = B.vgg19_plan(B.make_config(B.BF16, 100, 224, 224, 4096, 1000), False)
+    assert fwd16 == fwd
     tr = B.vgg19_plan(cfg, True)
     # 47 convolutions = 16 forward + 16 weight gradients + 15 data gradients (none for the first layer)
     assert tr.count(1) + tr.count(2) + tr.count(3) == gold["convolution"][1] == 47
