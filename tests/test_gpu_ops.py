@@ -245,6 +245,86 @@ def _patches(t_nchw, n, h, w):
     return out
 
 
+@pytest.mark.parametrize("shape,kernel", [((42, 28, 28, 64, 512), 4), ((11, 56, 56, 64, 512), 5), ((33, 32, 32, 64, 512), 4)])
+def test_conv3x3_bf16_weights_in_registers_element_by_element(shape, kernel):
+    """The weights-in-registers kernel at sizes the oracle computes whole: just over 512 tiles of 256 pixels x 128
+    channels (the smallest launches that take it), consecutive-pixel tiles with both halo sizes and patch tiles.
+    Forward (plain stores straight from registers), forward with the fused pool where the size allows it, and
+    the data gradient of the mirrored layer with its mask."""
+    dtype = B.BF16
+    N, H, W, Cin, Cout = shape
+    assert B.vgg_conv3x3_plan(B.PLAN_FWD, dtype, N, H, W, Cin, Cout)[0] == kernel
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=sum(shape))
+    ref = R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=True)
+    x = to_nhwc(d["x"], dtype)
+    wp = _pack(dtype, d["w"])
+    y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, wp, dev(d["b"]), y, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
+    if H % 16 == 0 and W % 16 == 0:
+        assert B.vgg_conv3x3_plan(B.PLAN_FWD_POOL, dtype, N, H, W, Cin, Cout)[0] == kernel
+        y2 = torch.empty_like(y)
+        po = torch.empty((N, H // 2, W // 2, Cout), dtype=TDT[dtype], device="cuda")
+        arg = torch.empty((N, H // 2, W // 2, Cout), dtype=torch.uint8, device="cuda")
+        B.vgg_conv3x3_fwd_pool(dtype, N, H, W, Cin, Cout, x, wp, dev(d["b"]), y2, po, 1, ws, argmax=arg)
+        torch.cuda.synchronize()
+        assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
+        po_chk = torch.empty_like(po)
+        arg_chk = torch.empty_like(arg)
+        B.vgg_maxpool2x2(dtype, N, H, W, Cout, y, po_chk, arg_chk)
+        torch.cuda.synchronize()
+        assert torch.equal(po.view(torch.int16), po_chk.view(torch.int16)) and torch.equal(arg, arg_chk)
+    # data gradient of the layer with the channel counts swapped: the same implicit GEMM on the flipped packing
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_DATA, dtype, N, H, W, Cout, Cin)[0] == kernel
+    d = synth.conv_layer_inputs(N, H, W, Cout, Cin, seed=sum(shape) + 1)
+    refd = R.conv3x3_bwd_data(d["dy"], d["w"])
+    g = to_nhwc(d["dy"], dtype)
+    dx = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+    wsd = ws_bytes(B.vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cout, Cin))
+    wtf = _pack(dtype, d["w"], flip=1)
+    xsrc = to_nhwc(d["x"], dtype)
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cout, Cin, g, wtf, xsrc, dx, wsd)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(dx), refd * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
+
+
+def test_conv3x3_bf16_320_pixel_tiles_element_by_element():
+    """The 320-pixel tiles (one workgroup per compute unit) at a size the oracle computes whole: 84 images of
+    14x14 give 52 such tiles x 4 column tiles, tiles that cross image rows and images, and a ragged last tile.
+    Forward on 128 -> 512 channels, data gradient (with and without mask) on 512 -> 128, each checked to be
+    the launch that takes that kernel."""
+    dtype = B.BF16
+    N, H, W = 84, 14, 14
+    # forward
+    Cin, Cout = 128, 512
+    assert B.vgg_conv3x3_plan(B.PLAN_FWD, dtype, N, H, W, Cin, Cout)[:2] in ([6, 320], [7, 320])
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=8414)
+    x = to_nhwc(d["x"], dtype)
+    y = torch.empty((N, H, W, Cout), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, Cout, x, _pack(dtype, d["w"]), dev(d["b"]), y, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y), R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=True)) <= TOL[dtype]
+    # data gradient
+    Cin, Cout = 512, 128
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_DATA, dtype, N, H, W, Cin, Cout)[:2] in ([6, 320], [7, 320])
+    d = synth.conv_layer_inputs(N, H, W, Cin, Cout, seed=8415)
+    ref = R.conv3x3_bwd_data(d["dy"], d["w"])
+    g = to_nhwc(d["dy"], dtype)
+    dx = torch.empty((N, H, W, Cin), dtype=TDT[dtype], device="cuda")
+    ws = ws_bytes(B.vgg_conv3x3_bwd_data_workspace_bytes(dtype, N, H, W, Cin, Cout))
+    wtf = _pack(dtype, d["w"], flip=1)
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, None, dx, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(dx), ref) <= TOL[dtype]
+    xsrc = to_nhwc(d["x"], dtype)
+    B.vgg_conv3x3_bwd_data(dtype, N, H, W, Cin, Cout, g, wtf, xsrc, dx, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(dx), ref * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("shape", FULL_SIZE_LAYERS)
 def test_conv3x3_bf16_full_size_on_sampled_pixels(shape):
     """Forward and data gradient at the benchmark's sizes, in the launch configuration it times; the oracle
