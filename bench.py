@@ -305,6 +305,47 @@ def mfma_loop_ceiling():
     return out
 
 
+def operand_sensitivity(steps):
+    """The forward benchmark's dominant kernel on one layer (bf16, 512 -> 512 channels, 28x28, batch 100, bias + ReLU,
+    through vgg_conv3x3_fwd) with three kinds of operand values: N(0,1) activations with He-normal weights, the same
+    activations after a ReLU (half of them zero, as inside the network) and one constant everywhere.  Same launches,
+    same instruction stream: the spread is what the chip's power management does with the switching activity of
+    the data, and it bounds what `roofline.frac` can reach on real values."""
+    import torch
+    from paper_1810_09868_amd import binding as B
+    N, H, W, Cin, Cout = 100, 28, 28, 512, 512
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    x0 = torch.randn((N, H, W, Cin), device="cuda", generator=gen)
+    w0 = torch.randn((Cout, Cin, 3, 3), device="cuda", generator=gen) * (2.0 / (9 * Cin)) ** 0.5
+    bias = torch.full((Cout,), 0.01, device="cuda")
+    y = torch.empty((N, H, W, Cout), dtype=torch.bfloat16, device="cuda")
+    wsb = B.vgg_conv3x3_fwd_workspace_bytes(B.BF16, N, H, W, Cin, Cout)
+    ws = torch.empty((max(wsb, 256),), dtype=torch.uint8, device="cuda") if wsb else None
+    flops = 2.0 * N * H * W * 9 * Cin * Cout
+    out = {"workload": "3x3 conv 512->512, 28x28, batch 100, bf16, bias+ReLU (vgg_conv3x3_fwd)",
+           "kernel": B.vgg_conv3x3_plan(B.PLAN_FWD, B.BF16, N, H, W, Cin, Cout)[0]}
+    cases = (("normal_activations", x0, w0), ("relu_activations", x0.clamp(min=0), w0),
+             ("constant", torch.full_like(x0, 1.0), torch.full_like(w0, 1.0 / (9 * Cin))))
+    for name, xf, wf in cases:
+        x = xf.to(torch.bfloat16)
+        w = torch.empty((9, Cout, Cin), dtype=torch.bfloat16, device="cuda")
+        B.vgg_conv_pack_weights(B.BF16, Cin, Cout, wf, w, 0)
+        for _ in range(3):
+            B.vgg_conv3x3_fwd(B.BF16, N, H, W, Cin, Cout, x, w, bias, y, 1, ws)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            B.vgg_conv3x3_fwd(B.BF16, N, H, W, Cin, Cout, x, w, bias, y, 1, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        out[name + "_tflops"] = round(flops / (ms * 1e-3) / 1e12, 1)
+    return out
+
+
 def cpu_baseline(inp, images):
     from oracle import vgg_ref as R
     t0 = time.perf_counter()
@@ -391,6 +432,8 @@ def main():
         out["train_step_bf16"] = run_train_bench(a.batch, max(2, a.steps // 2), dtype_name="bf16", extras=False)
         out["batch_sweep"] = batch_sweep(a.dtype, (1, 10), max(5, a.steps))
     out["mfma_loop_ceiling"] = mfma_loop_ceiling()
+    if not a.no_secondary:
+        out["operand_sensitivity"] = operand_sensitivity(max(10, a.steps))
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, min(a.cpu_images, a.batch))
     print(json.dumps(out))
