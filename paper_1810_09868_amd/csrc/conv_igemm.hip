@@ -152,16 +152,19 @@ __device__ __forceinline__ void conv_partial_epilogue(f32x16 (&acc)[BM / WM / 32
 }
 
 // Epilogue shared by the kernels below; called by every thread of the workgroup once all MFMAs are
-// issued.  smem is the start of the workgroup's dynamic LDS, which is reused here.
-template <typename T, int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
-                                              const TileOrigin &org, char *smem, int n0)
+// issued.  smem is the start of the workgroup's dynamic LDS, which is reused here.  How the accumulators
+// are spread over lanes and registers is the caller's business: stage(i, j0, epi, lo) writes pixel block i
+// (32 tile rows) x the 128 bytes of columns that start at MFMA column tile j0 of the wave into the wave's
+// staging block (row r at epi + r * kEpiRow), each value raised to at least lo; each_element(f) calls
+// f(tile row, column within the wave's 64- or 128-column range, value) for everything the lane holds.
+template <typename T, int BM, int BN, int WM, int WN, typename Stage, typename EachElement>
+__device__ __forceinline__ void conv_epilogue_impl(Stage stage, EachElement each_element, const ConvArgs &p,
+                                                   const TileOrigin &org, char *smem, int n0)
 {
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6;
     const int wm = wv % WM, wn = wv / WM;
-    const int r = lane & 31, khalf = lane >> 5;
     // Epilogue: ReLU, optional (mask > 0) factor, convert, store (the bias is already in the sums).
     // A lane owns four-channel runs of one pixel (see init_acc).  Each wave passes 32 pixels x 128
     // bytes at a time through a private LDS block so that every lane then stores 16 contiguous bytes.
@@ -180,17 +183,7 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int j0 = 0; j0 < TN; j0 += TJ) {
-#pragma unroll
-                for (int jj = 0; jj < TJ; ++jj) {
-#pragma unroll
-                    for (int a = 0; a < 4; ++a) {
-                        // (no ReLU: maximum with -inf, one instruction either way)
-                        const f32x16 &t = acc[i][j0 + jj];
-                        store4(reinterpret_cast<T *>(epi + r * kEpiRow) + jj * 32 + a * 8 + khalf * 4,
-                               fmaxf(t[a * 4], lo), fmaxf(t[a * 4 + 1], lo), fmaxf(t[a * 4 + 2], lo),
-                               fmaxf(t[a * 4 + 3], lo));
-                    }
-                }
+                stage(i, j0, epi, lo);   // (no ReLU: maximum with -inf, one instruction either way)
                 const int colbase = n0 + wn * (BN / WN) + j0 * 32 + seg * VEC;
                 if (p.pool) {
                     // Patch tiles: these 32 rows are two patch rows of 16 pixels, i.e. eight whole 2x2
@@ -245,25 +238,48 @@ __device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / W
         return;
     }
     // channel counts that do not allow 16-byte stores: element-wise
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = tile_pixel(p.g, org, wm * (BM / WM) + i * 32 + r);
-        if (m < 0) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int col = n0 + wn * (BN / WN) + j * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                if (col < p.Cout) {
-                    float v = acc[i][j][e];
-                    if (p.relu) v = fmaxf(v, 0.f);
-                    const size_t o = (size_t)m * p.Cout + col;
-                    if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
-                    Elem<T>::store(y + o, v);
-                }
-            }
+    each_element([&](int row, int c, float v) __attribute__((always_inline)) {
+        const int m = tile_pixel(p.g, org, row);
+        const int col = n0 + wn * (BN / WN) + c;
+        if (m >= 0 && col < p.Cout) {
+            if (p.relu) v = fmaxf(v, 0.f);
+            const size_t o = (size_t)m * p.Cout + col;
+            if (mask && !(Elem<T>::load(mask + o) > 0.f)) v = 0.f;
+            Elem<T>::store(y + o, v);
         }
-    }
+    });
+}
+
+// ... for 32x32 accumulators (see init_acc for their layout)
+template <typename T, int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void conv_epilogue(f32x16 (&acc)[BM / WM / 32][BN / WN / 32], const ConvArgs &p,
+                                              const TileOrigin &org, char *smem, int n0)
+{
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int TJ = 128 / (int)sizeof(T) / 32;   // MFMA column tiles per staged pass
+    const int lane = threadIdx.x & 63, wm = (threadIdx.x >> 6) % WM;
+    const int r = lane & 31, khalf = lane >> 5;
+    conv_epilogue_impl<T, BM, BN, WM, WN>(
+        [&](int i, int j0, char *epi, float lo) __attribute__((always_inline)) {
+#pragma unroll
+            for (int jj = 0; jj < TJ; ++jj)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x16 &t = acc[i][j0 + jj];
+                    store4(reinterpret_cast<T *>(epi + r * kEpiRow) + jj * 32 + a * 8 + khalf * 4, fmaxf(t[a * 4], lo),
+                           fmaxf(t[a * 4 + 1], lo), fmaxf(t[a * 4 + 2], lo), fmaxf(t[a * 4 + 3], lo));
+                }
+        },
+        [&](auto f) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        f(wm * (BM / WM) + i * 32 + r, j * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3), acc[i][j][e]);
+        },
+        p, org, smem, n0);
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
@@ -609,25 +625,40 @@ __global__ __launch_bounds__(WM *WN * 64, WM *WN == 8 ? 4 : 3) void conv3x3_igem
 
 // ---------------------------------------------------------------------------
 // bf16 variant with the weight fragments in registers.  The blocked weight layout (packed_w_index)
-// makes the 32 channels x 16 contraction indices of an MFMA operand 1 KB of contiguous memory, so a
-// wave loads its weight fragments straight from global memory (L2), a few MFMA steps ahead, into a
-// small ring of registers; LDS holds only the input halo.  Compared with the kernel above this
-// removes the weights from LDS traffic (half the fragment reads), the per-stage weight copies and
-// their barrier: one barrier per 32-channel chunk, i.e. per 144 MFMAs of a wave.
+// keeps the 16 contraction indices of a block contiguous per output channel (32 bytes), so a wave loads
+// its weight fragments straight from global memory (L2), two taps ahead, into a small ring of
+// registers; LDS holds only the input halo.  Compared with the kernel above this removes the weights
+// from LDS traffic (half the fragment reads), the per-stage weight copies and their barrier: one
+// barrier per 32-channel chunk, i.e. per 288 MFMAs of a wave.
 //
-// Workgroup: WM x WN waves, each a (32 TM)-pixel x 64-channel sub-tile: TM = 4 (4 x 2 MFMA blocks, 128
-// accumulator registers) with two workgroups per CU, or TM = 5 with one workgroup per CU and twice the
-// registers per wave, for launches whose 256-pixel tiles would number between one and two per CU (then
-// the CUs with two need twice as long as those with one: 320-pixel tiles give every CU at most one).
-// A chunk is 18 steps (tap, k-group); a step is TM halo-fragment reads and 2 TM MFMAs.  The halo of a chunk is copied by global_load_lds_dwordx4 into one
-// of two buffers a whole chunk ahead; rows are 80 bytes (64 data + 16 pad, conflict-free fragment
+// MFMA shape: v_mfma_f32_16x16x32_bf16, each contracting all 32 channels of a chunk.  It does half the
+// accumulator traffic per multiply-add of the 32x32x16 shape, and under the power that the operand values
+// of this workload draw the chip sustains it at a higher rate (bare loops on random operands: 2.0 against
+// 1.87 PFLOP/s; this kernel: +4.5 % over the same schedule on 32x32x16).
+// Lane 16 g + q of a wave holds, of a pixel-block fragment, channels 8 g .. 8 g + 7 of pixel q (16 bytes of
+// the pixel's 64-byte LDS row); of a weight fragment, the same contraction indices of output channel q (16
+// bytes of the blocked layout: block 2 chunk + g / 2, half g % 2); of a 16x16 accumulator, channels
+// 4 g .. 4 g + 3 of pixel q.
+//
+// Workgroup: WM x WN waves, each a (32 TM)-pixel x 64-channel sub-tile, i.e. 2 TM pixel blocks x 4 channel
+// blocks of 16: TM = 4 (128 accumulator registers) with two workgroups per CU, or TM = 5 with one
+// workgroup per CU and twice the registers per wave, for launches whose 256-pixel tiles would number
+// between one and two per CU (then the CUs with two need twice as long as those with one: 320-pixel
+// tiles give every CU at most one).
+// A chunk is nine steps, one per tap; a step is 2 TM halo-fragment reads and 8 TM MFMAs.  The four weight
+// fragments of a tap are requested two taps ahead into a ring of three taps; halo fragments one per pixel
+// block, LA blocks ahead into a ring of LA + 1.  The halo of a chunk is copied by global_load_lds_dwordx4
+// into one of two buffers a whole chunk ahead; rows are 80 bytes (64 data + 16 pad, conflict-free fragment
 // reads at addresses that are a per-lane base plus an offset per tap); the copy treats a buffer as
-// consecutive 16-byte slots, slot s = row s / 5, segment s % 5, every lane supplying the source
-// address of its slot (pad slots and rows outside the image read a block of zeros).
-// All vector-memory waits are written by hand (the loads are inline assembly), counting the
-// operations issued since the one waited for; the schedule is static, so the counts are constants.
-// The order of the sums (chunk, kernel row, tap, k-group) is that of the kernel above: results are
-// bit-identical.
+// consecutive 16-byte slots, slot s = row s / 5, segment s % 5, every lane supplying the source address of
+// its slot (pad slots and rows outside the image read a block of zeros).  Once the last halo fragment of a
+// chunk has been requested (LA blocks before the chunk ends) the workgroup synchronises, reads on from the
+// other buffer and copies the halo of the chunk after next into the one it has left.
+// Every other instruction of a step is issued right after an MFMA, in its shadow: a wave issues in order,
+// and issued as a block before the MFMAs they would leave the matrix pipe idle whenever the SIMD's other
+// wave is not multiplying.
+// All vector-memory waits are written by hand (the loads are inline assembly), counting the loads and
+// copies issued since the one waited for; the schedule is static, so the counts are constants.
 // ---------------------------------------------------------------------------
 constexpr int kWregHaloRows = 384;      // halo rows of the weights-in-registers kernel (64 KB of LDS) ...
 constexpr int kWregHaloRowsBig = 448;   // ... and of its variant for tiles that straddle images (72 KB)
@@ -639,24 +670,28 @@ __device__ __forceinline__ void for_each_step(F &&f, std::integer_sequence<int, 
     (f(std::integral_constant<int, S>{}), ...);
 }
 
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
 template <int WM, int WN, int SA, int TM, int OCC>
 __global__ __launch_bounds__(WM *WN * 64, OCC) void conv3x3_igemm_wreg_kernel(ConvArgs p)
 {
     typedef bf16_t T;
-    constexpr int NW = WM * WN, NT = NW * 64, BM = WM * TM * 32, BN = WN * 64, TN = 2;
+    constexpr int NW = WM * WN, NT = NW * 64, BM = WM * TM * 32, BN = WN * 64;
+    constexpr int NI = 2 * TM, NJ = 4;           // 16-pixel and 16-channel blocks per wave
     constexpr int KC = 32;                       // channels per chunk (one 64-byte LDS row)
     constexpr int NQ = (SA * 5 + NT - 1) / NT;   // halo copies per thread and chunk
     constexpr int ABUF = NQ * NT * 16;           // bytes per halo buffer (>= SA * 80)
-    constexpr int R = 6, D = R - 1;              // ring of weight steps in registers, prefetch distance
-    constexpr int STEPS = 18;                    // (tap, k-group) steps per chunk
-    static_assert(STEPS % R == 0, "ring positions must repeat every chunk");
+    constexpr int TAPS = 9, RB = 3;              // taps of weight fragments in registers
+    constexpr int LA = NI % 4 == 0 ? 3 : 4, RA = LA + 1;
+    static_assert(TAPS % RB == 0 && (TAPS * NI) % RA == 0, "ring positions must repeat every chunk");
+    static_assert(NJ <= NI - LA && NQ <= 3 * LA, "weight loads and halo copies share the slots after the MFMAs");
 
     extern __shared__ __align__(16) char smem[];   // [2][ABUF]
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wv % WM, wn = wv / WM;
-    const int r = lane & 31, khalf = lane >> 5;
-    // (XCD-aware numbering as in the kernel above)
+    const int q = lane & 15, g = lane >> 4;
+    // (XCD-aware numbering as in the kernels above)
     const int nblk = gridDim.x, xcd = blockIdx.x & 7;
     const int bid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + (blockIdx.x >> 3);
     const int tile_n = bid % p.tiles_n, tile_m = bid / p.tiles_n;
@@ -669,180 +704,204 @@ __global__ __launch_bounds__(WM *WN * 64, OCC) void conv3x3_igemm_wreg_kernel(Co
     // source of each of this lane's halo slots (chunk 0)
     const char *asrc[NQ];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int slot = (q * NW + wv) * 64 + lane;
+    for (int k = 0; k < NQ; ++k) {
+        const int slot = (k * NW + wv) * 64 + lane;
         const int row = slot / 5, seg = slot - row * 5;
         const int px = (row < p.g.S && seg < 4) ? halo_pixel(p.g, org, row) : -1;
-        asrc[q] = px < 0 ? reinterpret_cast<const char *>(kZeroBlock) : p.x + (size_t)px * xrow + seg * 16;
+        asrc[k] = px < 0 ? reinterpret_cast<const char *>(kZeroBlock) : p.x + (size_t)px * xrow + seg * 16;
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
-    auto copy_halo = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ABUF + (q * NW + wv) * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[q]) : "m0", "memory");
-        }
-    };
-    // the copies of one chunk in 2 TM parts (one after each MFMA of a step)
-    auto copy_halo_part = [&](int buf, int part) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            if (q * (2 * TM) / NQ != part) continue;
-            const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ABUF + (q * NW + wv) * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[q]) : "m0", "memory");
-        }
+    auto copy_slot = [&](int buf, int k) __attribute__((always_inline)) {
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ABUF + (k * NW + wv) * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(asrc[k]) : "m0", "memory");
     };
     auto next_chunk = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) asrc[q] += KC * sizeof(T);
+        for (int k = 0; k < NQ; ++k) asrc[k] += KC * sizeof(T);
     };
 
-    // byte address (inside a buffer) of tap (0,0) of this lane's pixel rows, k-half included
-    int arow[TM];
+    // byte address (inside a buffer) of tap (0,0) of this lane's pixels, its 16 bytes of the row included
+    int arow[NI];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < NI; ++i) {
         int m, hrow;
-        tile_row(p.g, org, wm * (TM * 32) + i * 32 + r, m, hrow);
-        arow[i] = hrow * kRowBytes + khalf * 16;
+        tile_row(p.g, org, wm * (TM * 32) + i * 16 + q, m, hrow);
+        arow[i] = hrow * kRowBytes + g * 16;
     }
 
-    // weight fragment (tap t, k block kb, channels c..c+31): 1 KB at ((t*KB + kb)*Cout + c) * 32 bytes
+    // weight fragment (tap t, chunk c, channels ch .. ch + 15): lane's 16 bytes at
+    // ((t * KB + 2 c + g / 2) * Cout + ch + q) * 32 + (g % 2) * 16
     const int KB = p.CinP / 16;
-    unsigned voff[TN];
+    unsigned voff[NJ];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) voff[j] = (unsigned)min(n0 + wn * 64 + j * 32 + r, p.Cout - 1) * 32u + khalf * 16;   // channels past Cout are never stored
-    u32x4 bq[R][TN];
-    auto load_w = [&](int chunk, int t, int g, u32x4(&dst)[TN]) __attribute__((always_inline)) {
-        const char *sb = p.w + ((size_t)(t * KB + chunk * 2 + g) * p.Cout) * 32;
+    for (int j = 0; j < NJ; ++j)   // channels past Cout are never stored
+        voff[j] = (unsigned)min(n0 + wn * 64 + j * 16 + q, p.Cout - 1) * 32u + (g & 1) * 16 + (unsigned)(g >> 1) * p.Cout * 32u;
+    u32x4 bq[RB][NJ];
+    auto load_w = [&](const char *sb, u32x4(&dst)[NJ]) __attribute__((always_inline)) {
         const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)sb);
         const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uintptr_t)sb >> 32));
         const unsigned long long sbase = ((unsigned long long)hi << 32) | lo;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < NJ; ++j)
             asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst[j]) : "v"(voff[j]), "s"(sbase) : "memory");
     };
 
-    f32x16 acc[TM][TN];
-    init_acc<BN, WN>(acc, p, n0, wn, khalf);
+    // Accumulators start at the bias (requested here into the first pixel block, copied to the others once
+    // the loads have had time to land).
+    f32x4v acc[NI][NJ];
+    {
+        const int c0 = n0 + wn * 64 + g * 4;
+        if (!p.bias || p.part) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[0][j] = f32x4v{0.f, 0.f, 0.f, 0.f};
+        } else if ((p.Cout & 3) == 0) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[0][j] = *reinterpret_cast<const f32x4v *>(p.bias + min(c0 + j * 16, p.Cout - 4));
+        } else {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[0][j][e] = p.bias[min(c0 + j * 16 + e, p.Cout - 1)];
+        }
+    }
 
-    // prologue: the first two halo chunks and the first D weight steps
-    copy_halo(0);
-    if (nchunks > 1) { next_chunk(); copy_halo(1); }
-    for_each_step([&](auto ic) {
-        constexpr int s = decltype(ic)::value;
-        load_w(0, s / 2, s % 2, bq[s % R]);
-    }, std::make_integer_sequence<int, D>{});
+    // prologue: the first two halo chunks and the weights of the first two taps
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) copy_slot(0, k);
+    if (nchunks > 1) {
+        next_chunk();
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) copy_slot(1, k);
+    }
+    const long long w_tap = (long long)KB * p.Cout * 32;            // next tap of the same chunk
+    const long long w_c = 2ll * p.Cout * 32 - 8 * w_tap;            // last tap -> first tap of the next chunk
+    const long long w_same = -8 * w_tap;                            // ... of the same chunk again (past the end)
+    load_w(p.w, bq[0]);
+    load_w(p.w + w_tap, bq[1]);
+    const char *wnext = p.w + 2 * w_tap;                            // the fragments requested next: tap 2 of chunk 0
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    spread_acc(acc);
-
-    u32x4 af[2][TM];
-    auto read_halo = [&](int buf, int t, int g, u32x4(&dst)[TM]) __attribute__((always_inline)) {
-        const int kh = t / 3, kw = t - kh * 3;
-        const char *base = smem + buf * ABUF + (kh * pitch + kw) * kRowBytes + g * 32;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) dst[i] = *reinterpret_cast<const u32x4 *>(base + arow[i]);
-    };
-    read_halo(0, 0, 0, af[0]);
+    for (int i = 1; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = acc[0][j];
 
-    // Instruction order inside a step: a wave issues in order and an MFMA holds the matrix pipe for 32
-    // cycles, so every other instruction of a step (the four halo-fragment reads of the next step, the two
-    // weight loads of step s + D) is issued right after an MFMA, in its shadow; issued as a block before
-    // the MFMAs they would leave the pipe idle whenever the SIMD's other wave is not multiplying.
-    // The weight fragments are requested in the order (chunk, tap, k-group); the scalar pointer to the
-    // next one moves by one of three constants (next k-group, next tap, next chunk), so a step spends two
-    // scalar additions on it.
-    const long long w_g = (long long)p.Cout * 32;                     // next k-group of the same tap
-    const long long w_t = (long long)KB * p.Cout * 32 - w_g;          // k-group 1 -> k-group 0 of the next tap
-    const long long w_c = 2 * w_g - 8 * (w_t + w_g) - w_g;            // last tap, k-group 1 -> first tap of the next chunk
-    const long long w_same = w_c - 2 * w_g;                           // ... of the same chunk again (past the end)
-    const char *wnext = p.w + (size_t)((D / 2) * KB + D % 2) * p.Cout * 32;   // step D of chunk 0 (D < 18)
+    u32x4 af[RA];
+#pragma unroll
+    for (int f = 0; f < LA; ++f) af[f] = *reinterpret_cast<const u32x4 *>(smem + arow[f]);   // tap 0, pixel blocks 0 .. LA - 1
+
     for (int c = 0; c < nchunks; ++c) {
         const int ab = c & 1;
         const long long w_wrap = c + 1 < nchunks ? w_c : w_same;
         for_each_step([&](auto ic) {
-            constexpr int s = decltype(ic)::value;
-            constexpr int sp = (s + D) % STEPS;   // step whose weights are requested during this one
-            // This step's two weight loads were issued during step s - D; since then came the loads of D - 1
-            // more steps and, when the last step of a chunk lies in between, its NQ halo copies (when it is
-            // step s - D itself: the copies issued after that step's second weight load, parts 4 and up).
-            constexpr int late_copies = NQ - ((4 * NQ + 2 * TM - 1) / (2 * TM));
-            constexpr int younger = 2 * (D - 1) + (s < D - 1 ? NQ : (s == D - 1 ? late_copies : 0));
-            u32x4 b0 = bq[s % R][0], b1 = bq[s % R][1];
-            asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b0), "+v"(b1) : "n"(younger));
-            if (s == STEPS - 1) {
-                // Every halo read of this chunk has been issued (the last ones during the previous step), and
-                // the wait above has also covered the next chunk's copies, issued a whole chunk ago.  After
-                // the barrier the other buffer is published and this one is free for the chunk after next.
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                if (c + 2 < nchunks) next_chunk();   // (past the end: the last chunk again, never read; keeps the wait counts static)
-            }
-            const int nbuf = s < STEPS - 1 ? ab : ab ^ 1;
-            constexpr int nt = ((s + 1) % STEPS) / 2, ng = (s + 1) % 2;
-            const char *abase = smem + nbuf * ABUF + ((nt / 3) * pitch + nt % 3) * kRowBytes + ng * 32;
+            constexpr int t = decltype(ic)::value;
+            // This tap's four weight fragments were requested during tap t - 2; since then came the four of tap
+            // t + 1 and, when the end of a chunk lies in between, its NQ halo copies.
+            constexpr int younger = NJ + (t < 2 ? NQ : 0);
+            u32x4 b0 = bq[t % RB][0], b1 = bq[t % RB][1], b2 = bq[t % RB][2], b3 = bq[t % RB][3];
+            asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b0), "+v"(b1), "+v"(b2), "+v"(b3) : "n"(younger));
             const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)wnext);
             const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uintptr_t)wnext >> 32));
             const unsigned long long sbase = ((unsigned long long)hi << 32) | lo;
-            wnext += sp == STEPS - 1 ? w_wrap : (sp % 2 == 0 ? w_g : w_t);
+            wnext += (t + 2) % TAPS == TAPS - 1 ? w_wrap : w_tap;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, af[s & 1][i]);
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b0), a, acc[i][0], 0, 0, 0);
+            for (int i = 0; i < NI; ++i) {
+                constexpr int first_next = NI - LA;   // the pixel block during which the first fragment of the next chunk is requested
+                if (t == TAPS - 1 && i == first_next) {
+                    // Every halo read of this chunk has been issued; the waits at the taps so far have covered
+                    // the next chunk's copies, issued a whole chunk ago.  After the barrier the other buffer is
+                    // published and this one is free for the chunk after next.
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    if (c + 2 < nchunks) next_chunk();   // (past the end: the last chunk again, never read; keeps the wait counts static)
+                }
+                const int f = t * NI + i;             // position in the chunk's sequence of halo fragments
+                const int fr = (f + LA) % (TAPS * NI), nt = fr / NI, ni = fr % NI;
+                const int nbuf = f + LA < TAPS * NI ? ab : ab ^ 1;
+                const char *abase = smem + nbuf * ABUF + ((nt / 3) * pitch + nt % 3) * kRowBytes;
+                const bf16x8 a = __builtin_bit_cast(bf16x8, af[f % RA]);
+                const bool copying = t == TAPS - 1 && i >= first_next;
+                acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0), a, acc[i][0], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                af[(s + 1) & 1][i] = *reinterpret_cast<const u32x4 *>(abase + arow[i]);
-                if (s == STEPS - 1) copy_halo_part(ab, 2 * i);       // (the copies into the freed buffer, spread over this step's MFMAs)
+                af[(f + LA) % RA] = *reinterpret_cast<const u32x4 *>(abase + arow[ni]);
                 __builtin_amdgcn_sched_barrier(0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b1), a, acc[i][1], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b1), a, acc[i][1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (s == STEPS - 1) copy_halo_part(ab, 2 * i + 1);
-                if (i < TN)
-                    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[sp % R][i]) : "v"(voff[i]), "s"(sbase) : "memory");
+                if (i < NJ)
+                    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[(t + 2) % RB][i]) : "v"(voff[i]), "s"(sbase) : "memory");
+                if (copying && (i - first_next) * 3 < NQ) copy_slot(ab, (i - first_next) * 3);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[i][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b2), a, acc[i][2], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (copying && (i - first_next) * 3 + 1 < NQ) copy_slot(ab, (i - first_next) * 3 + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[i][3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b3), a, acc[i][3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (copying && (i - first_next) * 3 + 2 < NQ) copy_slot(ab, (i - first_next) * 3 + 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }, std::make_integer_sequence<int, STEPS>{});
+        }, std::make_integer_sequence<int, TAPS>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the weight loads and halo copies issued past the end
+
+    const int wrow0 = wm * (TM * 32);
     if (p.pool || p.mask || !p.y || (p.Cout & 7)) {
-        conv_epilogue<T, BM, BN, WM, WN>(acc, p, org, smem, n0);
+        conv_epilogue_impl<T, BM, BN, WM, WN>(
+            [&](int i, int j0, char *epi, float lo) __attribute__((always_inline)) {
+                // (bf16: a pass is all 64 columns of the wave; pixel block i of 32 rows = 16-pixel blocks 2 i, 2 i + 1)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const f32x4v &t = acc[2 * i + h][j];
+                        store4(reinterpret_cast<T *>(epi + (h * 16 + q) * kEpiRow) + j * 16 + g * 4, fmaxf(t[0], lo), fmaxf(t[1], lo),
+                               fmaxf(t[2], lo), fmaxf(t[3], lo));
+                    }
+            },
+            [&](auto fn) __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) fn(wrow0 + i * 16 + q, j * 16 + g * 4 + e, acc[i][j][e]);
+            },
+            p, org, smem, n0);
         return;
     }
-    // Plain store epilogue (no pool, no mask): straight from registers, without the trip through LDS and its
-    // barrier.  A lane holds four consecutive channels of a pixel per accumulator quarter; it swaps one quarter
-    // with its partner lane (same pixel, the other four channels of each group of eight: lane +- 32,
-    // v_permlane32_swap) and then owns eight consecutive channels, 16 bytes, of two quarters.
+    // Plain store epilogue (no pool, no mask): straight from registers.  A lane holds four consecutive channels
+    // of a pixel per accumulator; lanes 16 apart (the next four channels of the same pixel) swap the values of
+    // one of two pixel blocks (v_permlane16_swap: the even row of 16 lanes ends up with eight channels of the
+    // first block, the odd row with eight channels of the second) and store 16 bytes each.
     {
         const float lo = p.relu ? 0.f : -__builtin_inff();
         T *y = reinterpret_cast<T *>(p.y);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = tile_pixel(p.g, org, wm * (TM * 32) + i * 32 + r);
+        for (int ip = 0; ip < NI / 2; ++ip) {
+            const int m = tile_pixel(p.g, org, wrow0 + (2 * ip + (g & 1)) * 16 + q);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                unsigned x[4][2];
+            for (int j = 0; j < NJ; ++j) {
+                typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                unsigned x[2][2];
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-                    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-                    const f32x2_t v0 = {fmaxf(acc[i][j][a * 4], lo), fmaxf(acc[i][j][a * 4 + 1], lo)};
-                    const f32x2_t v1 = {fmaxf(acc[i][j][a * 4 + 2], lo), fmaxf(acc[i][j][a * 4 + 3], lo)};
-                    x[a][0] = __builtin_bit_cast(unsigned, __builtin_convertvector(v0, bf16x2_t));
-                    x[a][1] = __builtin_bit_cast(unsigned, __builtin_convertvector(v1, bf16x2_t));
+                for (int h = 0; h < 2; ++h) {
+                    const f32x4v &t = acc[2 * ip + h][j];
+                    const f32x2_t v0 = {fmaxf(t[0], lo), fmaxf(t[1], lo)};
+                    const f32x2_t v1 = {fmaxf(t[2], lo), fmaxf(t[3], lo)};
+                    x[h][0] = __builtin_bit_cast(unsigned, __builtin_convertvector(v0, bf16x2_t));
+                    x[h][1] = __builtin_bit_cast(unsigned, __builtin_convertvector(v1, bf16x2_t));
                 }
 #pragma unroll
-                for (int ap = 0; ap < 2; ++ap) {
-                    // lanes 0-31 give their channels of quarter 2 ap + 1 and receive the partner's of quarter 2 ap
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const auto sw = __builtin_amdgcn_permlane32_swap(x[2 * ap][h], x[2 * ap + 1][h], false, false);
-                        x[2 * ap][h] = sw[0];
-                        x[2 * ap + 1][h] = sw[1];
-                    }
-                    const u32x4 v = {x[2 * ap][0], x[2 * ap][1], x[2 * ap + 1][0], x[2 * ap + 1][1]};
-                    const int col = n0 + wn * 64 + j * 32 + (2 * ap + khalf) * 8;
-                    if (m >= 0 && col < p.Cout) *reinterpret_cast<u32x4 *>(y + (size_t)m * p.Cout + col) = v;
+                for (int k = 0; k < 2; ++k) {
+                    const auto sw = __builtin_amdgcn_permlane16_swap(x[0][k], x[1][k], false, false);
+                    x[0][k] = sw[0];
+                    x[1][k] = sw[1];
                 }
+                const u32x4 v = {x[0][0], x[0][1], x[1][0], x[1][1]};
+                const int col = n0 + wn * 64 + j * 16 + (g >> 1) * 8;
+                if (m >= 0 && col < p.Cout) *reinterpret_cast<u32x4 *>(y + (size_t)m * p.Cout + col) = v;
             }
         }
     }
