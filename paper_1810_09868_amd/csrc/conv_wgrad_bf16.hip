@@ -6,30 +6,34 @@
 // (backward column of the appendix table: one more "convolution" per layer, plus a "reduce" for
 // the bias).  GEMM view per tap: rows = co, columns = ci, contraction over the pixels m.
 //
-// v_mfma_f32_32x32x16_bf16 wants, per lane, eight consecutive contraction indices of one row: eight
+// v_mfma_f32_16x16x32_bf16 wants, per lane, eight consecutive contraction indices of one row: eight
 // pixels of one channel.  Memory and LDS hold the opposite (a pixel's channels are contiguous), so
 // the fragments are fetched with the LDS transpose read ds_read_b64_tr_b16: within 16 lanes, lane i
 // receives element i%4 of the four 8-byte chunks that lanes i/4, i/4+4, i/4+8, i/4+12 point at.
 // Lane s of a group points at pixel s/4, channels 4(s%4).. of a 16-channel run: lane i then holds four
-// consecutive pixels of channel i.  Two such reads make a fragment; a tap only shifts the pixel rows
-// that the lanes point at, so all nine taps are served from one staged halo.
+// consecutive pixels of channel i.  Two such reads make a lane's eight pixels; the four 16-lane groups
+// of a wave take the four runs of eight pixels of two patch rows, so a fragment is 16 channels x the
+// 32 pixels of two patch rows.  A tap only shifts the pixel rows that the lanes point at, so all nine
+// taps are served from one staged halo.  (The 16x16x32 shape instead of 32x32x16: half the accumulator
+// traffic per multiply-add, which under the power this workload's operands draw is worth a few per
+// cent; same LDS reads, same registers.)
 //
 // A tile is a 4 x 16 patch of one image (patches may stick out at the right and bottom edge; what
-// is outside reads as zero) and its 6 x 18 halo: MFMA step s of a tile contracts the 16 pixels of
-// patch row s.  LDS rows are 160 bytes (64 channels + 32 bytes of padding: four consecutive pixel
-// rows then start 32 bytes apart in the banks and the transpose reads are conflict-free); since the
+// is outside reads as zero) and its 6 x 18 halo: MFMA step s of a tile contracts the 32 pixels of
+// patch rows 2s and 2s + 1.  LDS rows are 160 bytes (64 channels + 32 bytes of padding); since the
 // patch geometry is fixed, every fragment address is one per-lane base plus an immediate.
 //
 // A workgroup (4 waves) owns a 64(co) x 64(ci) block of all nine taps and a range of tiles.  Wave
-// = (ci half) x (taps 0-4 | taps 5-8); it multiplies both 32-row co tiles with its five or four x
-// fragments per step.  Staging: global_load_lds_dwordx4 straight into one of two LDS buffers, one
-// barrier per tile.  The block writes partial sums; a second kernel adds the partials of all
-// splits in a fixed order, so the result does not depend on scheduling.  The bias gradient comes
-// from two extra MFMAs per step against a fragment of ones, in the blocks of the first ci tile.
+// = (ci half) x (taps 0-4 | taps 5-8); it multiplies the four 16-row co fragments with the two 16-column
+// x fragments of each of its five or four taps per step.  Staging: global_load_lds_dwordx4 straight
+// into one of two LDS buffers, one barrier per tile.  The block writes partial sums; a second kernel
+// adds the partials of all splits in a fixed order, so the result does not depend on scheduling.  The
+// bias gradient comes from four extra MFMAs per step against a fragment of ones, in the blocks of the
+// first ci tile.
 //
 // At most 32 input channels (the first layer): the second ci half would be padding.  The two waves of
-// a tap group then both take the first half and alternate over the patch rows instead, and write
-// their sums as two separate partials.
+// a tap group then both take the first half and one step each, and write their sums as two separate
+// partials; with at most 16 input channels they also skip the second x fragment.
 #include "common.h"
 
 namespace vgg {
@@ -77,28 +81,29 @@ __device__ __forceinline__ bf16x8 tr_fragment(const char *lds_lo, const char *ld
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// Taps [T0, T0 + NT) of one wave.  DB: this wave also sums g over the pixels.  NARROW: see above.
-template <int T0, int NT, bool DB, bool NARROW>
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+// Taps [T0, T0 + NT) of one wave.  DB: this wave also sums g over the pixels.  NARROW: see above; NCI: x
+// fragments (16 input channels each) per tap.
+template <int T0, int NT, bool DB, bool NARROW, int NCI>
 __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *smem, int tco, int tci, int split)
 {
-    constexpr int NS = NARROW ? kTH / 2 : kTH;               // MFMA steps of this wave per tile
-    constexpr int SS = NARROW ? 2 : 1;                       // patch rows between them
+    constexpr int NS = NARROW ? 1 : kTH / 2;                 // MFMA steps (pairs of patch rows) of this wave per tile
+    constexpr int NCO = kCO / 16;                            // co fragments
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wi = wv & 1;                                   // ci half of this wave (NARROW: its first patch row)
+    const int wi = wv & 1;                                   // ci half of this wave (NARROW: its step)
     const int co0 = tco * kCO, ci0 = tci * kCI;
 
-    f32x16 acc[2][NT];
+    f32x4v acc[NCO][NCI][NT];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NCO; ++c)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int d = 0; d < NCI; ++d)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[c][t][e] = 0.f;
-    f32x16 accb[2];
+            for (int t = 0; t < NT; ++t) acc[c][d][t] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    f32x4v accb[NCO];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) accb[c][e] = 0.f;
+    for (int c = 0; c < NCO; ++c) accb[c] = f32x4v{0.f, 0.f, 0.f, 0.f};
 
     // Copies: lane covers bytes [16 L, 16 L + 16) of a buffer, L = 256 k + tid, k < kOps.  Which
     // tensor, pixel (relative to the patch origin) and channel segment that is never changes.
@@ -135,12 +140,13 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         }
     };
 
-    // Fragment addresses.  Lane 16 G + i points at pixel dx = 8 (G >> 1) + (i >> 2) (+4 for the second
-    // read) of a patch row and at the 8-byte chunk i & 3 of the 32-byte run G & 1 of a 32-channel tile.
+    // Fragment addresses.  Lane 16 G + i points at pixel dx = 8 (G & 1) + (i >> 2) (+4 for the second read) of
+    // patch row G >> 1 of the step's two, and at the 8-byte chunk i & 3 of a 32-byte run of 16 channels.
     const int G = lane >> 4, i = lane & 15;
-    const int lane_off = (8 * (G >> 1) + (i >> 2)) * kRow + (G & 1) * 32 + (i & 3) * 8;
-    const int g_off = lane_off + (NARROW ? wi * kTW * kRow : 0);                    // + co tile * 64 + (16 s + 4 h) * kRow
-    const int x_off = kGBytes + lane_off + (NARROW ? wi * kHW * kRow : wi * 64);    // + ((s + kh) * 18 + kw + 4 h) * kRow
+    const int g_off = ((G >> 1) * kTW + 8 * (G & 1) + (i >> 2)) * kRow + (i & 3) * 8 +
+                      (NARROW ? wi * 2 * kTW * kRow : 0);           // + co fragment * 32 + 32 s * kRow (+ 4 * kRow)
+    const int x_off = kGBytes + ((G >> 1) * kHW + 8 * (G & 1) + (i >> 2)) * kRow + (i & 3) * 8 +
+                      (NARROW ? wi * 2 * kHW * kRow : wi * 64);     // + x fragment * 32 + ((2 s + kh) * 18 + kw) * kRow (+ 4 * kRow)
 
     const int t_begin = split * p.tiles_per_split;
     const int t_end = min(t_begin + p.tiles_per_split, p.ntiles);
@@ -158,65 +164,85 @@ __device__ __forceinline__ void wgrad_bf16_body(const WgradBf16Args &p, char *sm
         if (tile + 1 < t_end) issue(tile + 1, smem + (buf ^ 1) * kBuf);
         const char *B = smem + buf * kBuf;
         // Fragments are requested one MFMA group ahead of their use (the LDS latency of a transpose read
-        // is longer than the two MFMAs a fragment feeds, and only two waves share a SIMD).
+        // is longer than the MFMAs a fragment feeds, and only two waves share a SIMD).
         auto g_frag = [&](int s, int c) __attribute__((always_inline)) {
-            return tr_fragment(B + g_off + c * 64 + (16 * SS * s) * kRow, B + g_off + c * 64 + (16 * SS * s + 4) * kRow);
+            const char *a = B + g_off + c * 32 + (2 * kTW * s) * kRow;
+            return tr_fragment(a, a + 4 * kRow);
         };
-        auto x_frag = [&](int s, int t) __attribute__((always_inline)) {
+        auto x_frag = [&](int s, int t, int d) __attribute__((always_inline)) {
             const int kh = (T0 + t) / 3, kw = (T0 + t) % 3;
-            const int ro = ((SS * s + kh) * kHW + kw) * kRow;
-            return tr_fragment(B + x_off + ro, B + x_off + ro + 4 * kRow);
+            const char *a = B + x_off + d * 32 + ((2 * s + kh) * kHW + kw) * kRow;
+            return tr_fragment(a, a + 4 * kRow);
         };
-        bf16x8 gf[2], gf_next[2], xf, xf_next;
-        gf_next[0] = g_frag(0, 0);
-        gf_next[1] = g_frag(0, 1);
-        xf_next = x_frag(0, 0);
+        bf16x8 gf[NCO], gf_next[NCO], xf[NCI], xf_next[NCI];
+#pragma unroll
+        for (int c = 0; c < NCO; ++c) gf_next[c] = g_frag(0, c);
+#pragma unroll
+        for (int d = 0; d < NCI; ++d) xf_next[d] = x_frag(0, 0, d);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            gf[0] = gf_next[0];
-            gf[1] = gf_next[1];
+#pragma unroll
+            for (int c = 0; c < NCO; ++c) gf[c] = gf_next[c];
             if (DB) {
 #pragma unroll
-                for (int c = 0; c < 2; ++c) accb[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], ones, accb[c], 0, 0, 0);
+                for (int c = 0; c < NCO; ++c) accb[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[c], ones, accb[c], 0, 0, 0);
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                xf = xf_next;
+#pragma unroll
+                for (int d = 0; d < NCI; ++d) xf[d] = xf_next[d];
                 if (t + 1 < NT) {
-                    xf_next = x_frag(s, t + 1);
+#pragma unroll
+                    for (int d = 0; d < NCI; ++d) xf_next[d] = x_frag(s, t + 1, d);
                 } else if (s + 1 < NS) {
-                    gf_next[0] = g_frag(s + 1, 0);
-                    gf_next[1] = g_frag(s + 1, 1);
-                    xf_next = x_frag(s + 1, 0);
+#pragma unroll
+                    for (int c = 0; c < NCO; ++c) gf_next[c] = g_frag(s + 1, c);
+#pragma unroll
+                    for (int d = 0; d < NCI; ++d) xf_next[d] = x_frag(s + 1, 0, d);
                 }
                 __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the MFMAs they overlap with
 #pragma unroll
-                for (int c = 0; c < 2; ++c) acc[c][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[c], xf, acc[c][t], 0, 0, 0);
+                for (int d = 0; d < NCI; ++d)
+#pragma unroll
+                    for (int c = 0; c < NCO; ++c)
+                        acc[c][d][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gf[c], xf[d], acc[c][d][t], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
 
-    // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (co), column l%32 (ci)
-    const int r = lane & 31, kp = lane >> 5;
-    const int ci = ci0 + (NARROW ? 0 : wi * 32) + r;
+    // accumulator layout: register e of lane l = row 4*(l/16) + e (co), column l%16 (ci)
+    const int ci = ci0 + (NARROW ? 0 : wi * 32) + i;
     if (NARROW) split = 2 * split + wi;                      // this wave's own partial
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NCO; ++c)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int d = 0; d < NCI; ++d)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int co = co0 + c * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
-                if (co < p.Cout && ci < p.CinP)
-                    p.part[(((size_t)split * 9 + T0 + t) * p.Cout + co) * p.CinP + ci] = acc[c][t][e];
-            }
-    if (DB && r == 0) {
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+                for (int e = 0; e < 4; ++e) {
+                    const int co = co0 + c * 16 + G * 4 + e;
+                    if (co < p.Cout && ci + d * 16 < p.CinP)
+                        p.part[(((size_t)split * 9 + T0 + t) * p.Cout + co) * p.CinP + ci + d * 16] = acc[c][d][t][e];
+                }
+    if (NCI == 1 && NARROW && i + 16 < p.CinP) {             // (columns this variant does not compute: zero)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int co = co0 + c * 32 + (e >> 2) * 8 + kp * 4 + (e & 3);
+        for (int c = 0; c < NCO; ++c)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int co = co0 + c * 16 + G * 4 + e;
+                    if (co < p.Cout) p.part[(((size_t)split * 9 + T0 + t) * p.Cout + co) * p.CinP + ci + 16] = 0.f;
+                }
+    }
+    if (DB && i == 0) {
+#pragma unroll
+        for (int c = 0; c < NCO; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int co = co0 + c * 16 + G * 4 + e;
                 if (co < p.Cout) p.dbpart[(size_t)split * p.Cout + co] = accb[c][e];
             }
     }
@@ -236,14 +262,20 @@ __global__ __launch_bounds__(kNW * 64, 2) void conv3x3_wgrad_bf16_kernel(WgradBf
     const int group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (p.narrow) {
-        if (group == 0) wgrad_bf16_body<0, 5, false, true>(p, smem, tco, tci, split);
-        else if (p.dbpart) wgrad_bf16_body<5, 4, true, true>(p, smem, tco, tci, split);   // each wave sums g over its own rows
-        else wgrad_bf16_body<5, 4, false, true>(p, smem, tco, tci, split);
+        if (p.XC <= 16) {   // (x holds at most 16 channels: one x fragment per tap)
+            if (group == 0) wgrad_bf16_body<0, 5, false, true, 1>(p, smem, tco, tci, split);
+            else if (p.dbpart) wgrad_bf16_body<5, 4, true, true, 1>(p, smem, tco, tci, split);   // each wave sums g over its own rows
+            else wgrad_bf16_body<5, 4, false, true, 1>(p, smem, tco, tci, split);
+            return;
+        }
+        if (group == 0) wgrad_bf16_body<0, 5, false, true, 2>(p, smem, tco, tci, split);
+        else if (p.dbpart) wgrad_bf16_body<5, 4, true, true, 2>(p, smem, tco, tci, split);
+        else wgrad_bf16_body<5, 4, false, true, 2>(p, smem, tco, tci, split);
         return;
     }
-    if (group == 0) wgrad_bf16_body<0, 5, false, false>(p, smem, tco, tci, split);
-    else if (p.dbpart && tci == 0 && wave == 2) wgrad_bf16_body<5, 4, true, false>(p, smem, tco, tci, split);
-    else wgrad_bf16_body<5, 4, false, false>(p, smem, tco, tci, split);
+    if (group == 0) wgrad_bf16_body<0, 5, false, false, 2>(p, smem, tco, tci, split);
+    else if (p.dbpart && tci == 0 && wave == 2) wgrad_bf16_body<5, 4, true, false, 2>(p, smem, tco, tci, split);
+    else wgrad_bf16_body<5, 4, false, false, 2>(p, smem, tco, tci, split);
 }
 
 void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
