@@ -355,7 +355,10 @@ int vgg19_plan(const vgg_config *cfg, int training, int *kinds_host, int cap);
  *       workgroup per compute unit; weight
  *       gradient: 100 linear tiles, 114 / 116 patches 14 / 16 pixels wide,
  *       103 the kernel for at most three input channels (fp32); 116 / 117
- *       the bf16 kernel and its variant for at most 32 input channels
+ *       the bf16 kernel and its variant for at most 32 input channels, 118
+ *       the bf16 kernel for at most three input channels on image widths
+ *       that are multiples of 16 ([4]..[6] then describe 117's plan, which
+ *       is what the workspace is sized for)
  *   [1] pixels per tile   [2] output channels per tile
  *   [3] 0: a tile is consecutive pixels, 1: a patch of one image
  *   [4] pixel tiles

@@ -36,9 +36,9 @@ void conv3x3_igemm_plan_info(int dtype, int N, int H, int W, int CinP, int Cout,
 size_t conv3x3_wgrad_workspace(int N, int H, int W, int Cin, int CinP, int Cout);
 void conv3x3_wgrad_plan_info(int N, int H, int W, int Cin, int CinP, int Cout, int info[5]);
 size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout);
-void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5]);
+void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5], int cin = 0);
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels = 0);
+                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels = 0, int cin = 0);
 // Channels per pixel of the NHWC copy of the images that the first layer's weight gradient reads: with bf16
 // operands one 16-byte segment (the three channels and five zeros) instead of a whole 64-byte row.
 inline int x0_channels(int dtype, int cinp0) { return dtype == VGG_BF16 ? 8 : cinp0; }
@@ -376,7 +376,7 @@ void run_train(const vgg_config *c, const PackedLayout &P, const WsLayout &L, co
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad_bf16(N, H, W, P.cinp[l], Cout, reinterpret_cast<const bf16_t *>(xin),
                                                      reinterpret_cast<const bf16_t *>(gbuf[cur]), F(gr + Pm.conv_w[l]),
                                                      F(gr + Pm.conv_b[l]), ws + L.wgws, L.wgws_bytes, s,
-                                                     l == 0 ? x0_channels(dt, P.cinp[0]) : 0));
+                                                     l == 0 ? x0_channels(dt, P.cinp[0]) : 0, Cin));
         else
             VGG_STEP(rec, K_WGRAD, conv3x3_wgrad(N, H, W, kConvCh[l][0], P.cinp[l], Cout, reinterpret_cast<const float *>(xin),
                                                 F(gbuf[cur]), F(gr + P.conv_w[l]), F(gr + P.conv_b[l]), ws + L.wgws,
@@ -663,18 +663,21 @@ int vgg_conv3x3_bwd_weight(int dtype, int N, int H, int W, int Cin, int Cout, co
     const int cp = padded_channels(dtype, Cin);
     hipStream_t s = (hipStream_t)stream;
     char *wsp = static_cast<char *>(ws);
+    int xc = 0;   // channels per pixel of the padded copy when fewer than cp (bf16, at most three channels: one 16-byte segment)
     if (cp != Cin) {
-        const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, cp, x, wsp, s);
+        const int to = dtype == VGG_BF16 && Cin <= 3 ? x0_channels(dtype, cp) : cp;
+        const int rc = pad_channels(dtype, (size_t)N * H * W, Cin, to, x, wsp, s);
         if (rc) return rc;
         x = wsp;
-        const size_t pad = round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);
+        if (to != cp) xc = to;
+        const size_t pad = round_up((size_t)N * H * W * cp * dtype_size(dtype), 256);   // (as the workspace query reserves it)
         wsp += pad;
         ws_bytes -= pad;
     }
     // (the launchers compare what is left of the workspace with the partial sums of the plan they run)
     if (dtype == VGG_BF16)
         return conv3x3_wgrad_bf16(N, H, W, cp, Cout, static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), dw, db, wsp,
-                                  ws_bytes, s);
+                                  ws_bytes, s, xc, Cin);
     return conv3x3_wgrad(N, H, W, Cin, cp, Cout, static_cast<const float *>(x), static_cast<const float *>(g), dw, db, wsp,
                          ws_bytes, s);
 }
@@ -981,7 +984,7 @@ int vgg_conv3x3_plan(int op, int dtype, int N, int H, int W, int Cin, int Cout, 
         int w[5];
         const int cp = padded_channels(dtype, Cin);
         if (dtype == VGG_F32) conv3x3_wgrad_plan_info(N, H, W, Cin, cp, Cout, w);
-        else conv3x3_wgrad_bf16_plan_info(N, H, W, cp, Cout, w);
+        else conv3x3_wgrad_bf16_plan_info(N, H, W, cp, Cout, w, Cin);
         info[0] = 100 + w[0];
         info[1] = w[0] == 14 ? 56 : 64;
         info[2] = 64;

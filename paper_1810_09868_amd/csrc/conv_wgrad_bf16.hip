@@ -278,6 +278,151 @@ __global__ __launch_bounds__(kNW * 64, 2) void conv3x3_wgrad_bf16_kernel(WgradBf
     else wgrad_bf16_body<5, 4, false, false, 2>(p, smem, tco, tci, split);
 }
 
+// ---------------------------------------------------------------------------
+// At most three input channels (the first layer; backward column of the appendix table, first "convolution"):
+// the contraction over the pixels has only 27 (tap, channel) columns, and the layer is bound by reading g
+// once.  No matrix unit, no LDS staging: a lane owns one output channel and keeps its 27 sums and the bias sum
+// in registers; g comes straight from global memory, two pixels of the lane's channel packed into a
+// register; the input pixels are the same for all lanes: one vector load per unit fetches them (one pixel per
+// lane, 54 lanes), v_readlane moves them to scalar registers, scalar instructions pack them into (pixel, next
+// pixel) pairs of one channel, and they enter v_dot2c_f32_bf16 as its scalar operand: one instruction adds two
+// pixels' products to a sum, in fp32.  (Fetching them with scalar loads instead was four times slower: the
+// scalar data cache is no place to stream an image through.)  A wave walks units of 16 pixels of an
+// image row (W must be a multiple of 16); the four waves of a workgroup add their sums through LDS and write one
+// partial per workgroup, [28][64 channels]; the partials are added by wgrad_launch_reduce and spread into the
+// [9][Cout][CinP] layout (zeros in the padding columns) by a small kernel.
+// ---------------------------------------------------------------------------
+constexpr int kThinK = 28;   // 27 (tap, channel) sums + the bias sum
+constexpr int kThinPx = 16;  // pixels per unit
+
+struct WgradThinArgs {
+    const bf16_t *x;   // [M][XC], channels 0..2 of a pixel in its first 8 bytes
+    const bf16_t *g;   // [M][Cout]
+    float *part;       // [gridDim.x][gridDim.y][28][64]
+    int H, W, XC, Cout, units, units_per_row;
+    FastDiv dUnitsPerRow, dH;
+};
+
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+
+typedef unsigned short u16x2v __attribute__((ext_vector_type(2)));
+typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+
+__global__ __launch_bounds__(256) void conv3x3_wgrad_bf16_thin_kernel(WgradThinArgs p)
+{
+    __shared__ float red[4][kThinK][64];
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int co = min((int)blockIdx.y * 64 + lane, p.Cout - 1);   // (lanes past Cout repeat the last channel; never stored)
+    float acc[kThinK];
+#pragma unroll
+    for (int k = 0; k < kThinK; ++k) acc[k] = 0.f;
+    auto dot2 = [](unsigned a, unsigned b, float c) __attribute__((always_inline)) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, a), __builtin_bit_cast(bf16x2v, b), c, false);
+    };
+    // (a, b) -> low halves of a and b / high halves of a and b in one register: one scalar pack instruction each
+    auto pack_lo = [](unsigned a, unsigned b) __attribute__((always_inline)) {
+        const u16x2v v = {(unsigned short)a, (unsigned short)b};
+        return __builtin_bit_cast(unsigned, v);
+    };
+    auto pack_hi = [](unsigned a, unsigned b) __attribute__((always_inline)) {
+        const u16x2v v = {(unsigned short)(a >> 16), (unsigned short)(b >> 16)};
+        return __builtin_bit_cast(unsigned, v);
+    };
+    // Input pixels of a unit: lane 18 kh + c (< 54) fetches the first 8 bytes (channels 0..3) of the pixel in image
+    // row h + kh - 1, column w0 + c - 1, or zeros when that lies outside the image.
+    const int xkh = lane / (kThinPx + 2), xc = lane - xkh * (kThinPx + 2);
+    // a unit's operands as loaded: this lane's channel of g for the 16 pixels, and this lane's input pixel
+    auto load_unit = [&](int u, unsigned(&gr16)[kThinPx], u32x2v &xv) __attribute__((always_inline)) {
+        const int row = fast_div(u, p.dUnitsPerRow);           // = n * H + h
+        const int w0 = (u - row * p.units_per_row) * kThinPx;
+        const int n = fast_div(row, p.dH), h = row - n * p.H;
+        const unsigned short *gr = reinterpret_cast<const unsigned short *>(p.g) + ((size_t)row * p.W + w0) * p.Cout + co;
+#pragma unroll
+        for (int j = 0; j < kThinPx; ++j) gr16[j] = gr[(size_t)j * p.Cout];
+        const int hh = h + xkh - 1, ww = w0 + xc - 1;
+        const bool in = xkh < 3 && (unsigned)hh < (unsigned)p.H && (unsigned)ww < (unsigned)p.W;
+        // (clamped address, loaded unconditionally: a load inside a branch is waited for where the branch ends)
+        const size_t pix = in ? (size_t)(n * p.H + hh) * p.W + ww : (size_t)row * p.W + w0;
+        const u32x2v v = *reinterpret_cast<const u32x2v *>(reinterpret_cast<const char *>(p.x) + pix * p.XC * sizeof(bf16_t));
+        xv = in ? v : u32x2v{0u, 0u};
+    };
+    const int first = blockIdx.x * 4 + wv, stride = gridDim.x * 4;
+    unsigned graw[kThinPx];          // the next unit's g, one pixel per register: packed only when the unit's turn comes
+    u32x2v xnext = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < kThinPx; ++j) graw[j] = 0u;
+    if (first < p.units) load_unit(first, graw, xnext);
+    for (int u = first; u < p.units; u += stride) {
+        // two pixels of this lane's channel per register
+        unsigned gp[kThinPx / 2];
+#pragma unroll
+        for (int j = 0; j < kThinPx / 2; ++j) gp[j] = graw[2 * j] | (graw[2 * j + 1] << 16);
+        const u32x2v xv = xnext;
+        asm volatile("" : "+v"(gp[0]), "+v"(gp[1]), "+v"(gp[2]), "+v"(gp[3]), "+v"(gp[4]), "+v"(gp[5]), "+v"(gp[6]), "+v"(gp[7]));
+        if (u + stride < p.units) load_unit(u + stride, graw, xnext);   // (one unit ahead: its latency overlaps this unit's arithmetic)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            // the 18 pixels under this kernel row move to scalar registers (they are the same for every lane) ...
+            unsigned s01[kThinPx + 2], s2[kThinPx + 2];
+#pragma unroll
+            for (int c = 0; c < kThinPx + 2; ++c) {
+                s01[c] = __builtin_amdgcn_readlane(xv[0], kh * (kThinPx + 2) + c);
+                s2[c] = __builtin_amdgcn_readlane(xv[1], kh * (kThinPx + 2) + c);
+            }
+            // ... and are packed there into (pixel, next pixel) pairs of each channel, for the 17 adjacent column pairs
+            unsigned b0[kThinPx + 1], b1[kThinPx + 1], b2[kThinPx + 1];
+#pragma unroll
+            for (int c = 0; c <= kThinPx; ++c) {
+                b0[c] = pack_lo(s01[c], s01[c + 1]);
+                b1[c] = pack_hi(s01[c], s01[c + 1]);
+                b2[c] = pack_lo(s2[c], s2[c + 1]);
+            }
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                for (int j = 0; j < kThinPx / 2; ++j) {
+                    const int c = 2 * j + kw;                  // output pixels 2j, 2j+1 see input columns c, c+1
+                    const int k = (kh * 3 + kw) * 3;
+                    acc[k] = dot2(gp[j], b0[c], acc[k]);
+                    acc[k + 1] = dot2(gp[j], b1[c], acc[k + 1]);
+                    acc[k + 2] = dot2(gp[j], b2[c], acc[k + 2]);
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < kThinPx / 2; ++j) acc[27] = dot2(gp[j], 0x3F803F80u, acc[27]);
+    }
+#pragma unroll
+    for (int k = 0; k < kThinK; ++k) red[wv][k][lane] = acc[k];
+    __syncthreads();
+    float *out = p.part + ((size_t)blockIdx.x * gridDim.y + blockIdx.y) * kThinK * 64;
+    for (int e = threadIdx.x; e < kThinK * 64; e += 256) {
+        const int k = e >> 6, l = e & 63;
+        out[e] = (red[0][k][l] + red[1][k][l]) + (red[2][k][l] + red[3][k][l]);
+    }
+}
+
+// sums [co tiles][28][64] -> dw [9][Cout][CinP] (columns >= 3: zero), db [Cout]
+__global__ __launch_bounds__(256) void wgrad_bf16_thin_spread_kernel(const float *sums, float *dw, float *db, int Cout, int CinP)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int n = 9 * Cout * CinP;
+    if (i < n) {
+        const int ci = i % CinP, co = (i / CinP) % Cout, t = i / (CinP * Cout);
+        dw[i] = ci < 3 ? sums[((size_t)(co >> 6) * kThinK + t * 3 + ci) * 64 + (co & 63)] : 0.f;
+    } else if (i < n + Cout && db) {
+        const int co = i - n;
+        db[co] = sums[((size_t)(co >> 6) * kThinK + 27) * 64 + (co & 63)];
+    }
+}
+
+// workgroups along x of the thin kernel's launch: about four per CU in all, at most one per four units
+inline int wgrad_thin_blocks(int units, int co_tiles)
+{
+    int b = (1024 + co_tiles - 1) / co_tiles;
+    if (b > (units + 3) / 4) b = (units + 3) / 4;
+    return b < 1 ? 1 : b;
+}
+
 void wgrad_bf16_plan(int N, int H, int W, int CinP, int Cout, WgradBf16Args &a)
 {
     a.N = N; a.H = H; a.W = W; a.CinP = CinP; a.Cout = Cout;
@@ -318,12 +463,18 @@ size_t conv3x3_wgrad_bf16_workspace(int N, int H, int W, int CinP, int Cout)
 }
 
 // For inspection: {kernel (16: 4 x 16 patches; 17: the same with both waves of a tap group on one channel
-// half), pixel tiles, partial results, tiles per split, workgroups}.
-void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5])
+// half; 18: the thin kernel, when the caller passes cin -- the other entries then still describe 17's plan,
+// which is what the workspace is sized for), pixel tiles, partial results, tiles per split, workgroups}.
+void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int info[5], int cin)
 {
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
     info[0] = a.narrow ? 17 : 16;
+    if (cin >= 1 && cin <= 3 && W % kThinPx == 0) {
+        const int co_tiles = (Cout + 63) / 64;
+        const int nb = wgrad_thin_blocks(N * H * (W / kThinPx), co_tiles);
+        if (wgrad_bf16_ws_bytes(a) >= ((size_t)nb + 1) * co_tiles * kThinK * 64 * sizeof(float)) info[0] = 18;
+    }
     info[1] = a.ntiles;
     info[2] = wgrad_bf16_partials(a);
     info[3] = a.tiles_per_split;
@@ -333,14 +484,38 @@ void conv3x3_wgrad_bf16_plan_info(int N, int H, int W, int CinP, int Cout, int i
 // x [M][CinP] bf16 (channels >= Cin are zero), g [M][Cout] bf16 -> dw [9][Cout][CinP] fp32, db [Cout] fp32 (may be null).
 // Cout and CinP must be multiples of 8 (16-byte channel segments).  x_channels (optional): x holds only that many
 // channels per pixel (a multiple of 8, at most CinP), the rest count as zero -- the first layer's three channels
-// need one 16-byte segment per pixel, not a whole 64-byte row.
+// need one 16-byte segment per pixel, not a whole 64-byte row.  cin (optional): the number of real input channels
+// when the caller knows it; one to three of them on an image whose width is a multiple of 16 take the thin kernel.
 int conv3x3_wgrad_bf16(int N, int H, int W, int CinP, int Cout, const bf16_t *x, const bf16_t *g, float *dw, float *db,
-                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels)
+                       void *ws, size_t ws_bytes, hipStream_t stream, int x_channels, int cin)
 {
     if (Cout % 8 || CinP % 8) return VGG_ERR_UNSUPPORTED;
     if (x_channels == 0) x_channels = CinP;
     if (x_channels % 8 || x_channels > CinP) return VGG_ERR_UNSUPPORTED;
     if ((long long)N * H * W >= (1ll << 31) / 2) return VGG_ERR_UNSUPPORTED;
+    if (cin >= 1 && cin <= 3 && W % kThinPx == 0) {
+        // (falls through to the general kernel when the caller's workspace, sized without knowing cin, is too small)
+        WgradThinArgs t;
+        t.x = x; t.g = g; t.H = H; t.W = W; t.XC = x_channels; t.Cout = Cout;
+        t.units_per_row = W / kThinPx;
+        t.units = N * H * t.units_per_row;
+        t.dUnitsPerRow = make_fast_div(t.units_per_row);
+        t.dH = make_fast_div(H);
+        const int co_tiles = (Cout + 63) / 64;
+        const int nb = wgrad_thin_blocks(t.units, co_tiles);
+        const size_t one = (size_t)co_tiles * kThinK * 64;
+        if (ws_bytes >= ((size_t)nb + 1) * one * sizeof(float)) {
+            t.part = static_cast<float *>(ws);
+            float *sums = t.part + (size_t)nb * one;
+            hipLaunchKernelGGL(conv3x3_wgrad_bf16_thin_kernel, dim3((unsigned)nb, (unsigned)co_tiles), dim3(256), 0, stream, t);
+            if (hipGetLastError() != hipSuccess) return VGG_ERR_LAUNCH;
+            wgrad_launch_reduce(t.part, sums, one, nullptr, nullptr, 0, nb, stream);
+            const int total = 9 * Cout * CinP + Cout;
+            hipLaunchKernelGGL(wgrad_bf16_thin_spread_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, sums, dw, db,
+                               Cout, CinP);
+            return launch_status();
+        }
+    }
     WgradBf16Args a;
     wgrad_bf16_plan(N, H, W, CinP, Cout, a);
     if (ws_bytes < wgrad_bf16_ws_bytes(a)) return VGG_ERR_WORKSPACE;

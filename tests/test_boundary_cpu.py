@@ -172,6 +172,10 @@ def test_weight_gradient_workspace_query_covers_the_plan_that_runs():
     assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 224, 224, 3, 64)[0] == 103
     assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 224, 224, 64, 64)[0] == 116
     assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.F32, 100, 56, 56, 256, 256)[0] == 114
+    # bf16: the thin kernel needs a width that is a multiple of 16; otherwise the 32-channel variant of the general one
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.BF16, 100, 224, 224, 3, 64)[0] == 118
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.BF16, 57, 9, 42, 3, 64)[0] == 117
+    assert B.vgg_conv3x3_plan(B.PLAN_BWD_WEIGHT, B.BF16, 100, 224, 224, 64, 64)[0] == 116
 
 
 def test_convolution_plan_query():

@@ -383,7 +383,14 @@ def _step_from_single_op_calls(inp, dtype, N, H, W, hidden, classes):
             d = up
         dwp = torch.empty((9, co, cp), device="cuda")
         db = torch.empty((co,), device="cuda")
-        B.vgg_conv3x3_bwd_weight(dtype, N, hh, ww, cin_arg, co, c.acts_in[l], d, dwp, db,
+        x_in = c.acts_in[l]
+        if l == 0 and dtype == B.BF16:
+            # The model hands the first layer's weight gradient the images themselves (three channels, which
+            # selects the kernel for thin layers), not the zero-padded copy its forward convolution read.
+            cin_arg = 3
+            x_in = torch.empty((N, hh, ww, 3), dtype=tdt, device="cuda")
+            B.vgg_nchw_to_nhwc(dtype, N, 3, hh, ww, 3, dev(inp.x), x_in)
+        B.vgg_conv3x3_bwd_weight(dtype, N, hh, ww, cin_arg, co, x_in, d, dwp, db,
                                  ws(B.vgg_conv3x3_bwd_weight_workspace_bytes(dtype, N, hh, ww, cin_arg, co)))
         g["conv_w"][l] = dwp[:, :, :ci].reshape(3, 3, co, ci).permute(2, 3, 0, 1).contiguous()
         g["conv_b"][l] = db
