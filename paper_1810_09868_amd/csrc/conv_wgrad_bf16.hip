@@ -281,14 +281,14 @@ __global__ __launch_bounds__(kNW * 64, 2) void conv3x3_wgrad_bf16_kernel(WgradBf
 // ---------------------------------------------------------------------------
 // At most three input channels (the first layer; backward column of the appendix table, first "convolution"):
 // the contraction over the pixels has only 27 (tap, channel) columns, and the layer is bound by reading g
-// once.  No matrix unit, no LDS staging: a lane owns one output channel and keeps its 27 sums and the bias sum
-// in registers; g comes straight from global memory, two pixels of the lane's channel packed into a
-// register; the input pixels are the same for all lanes: one vector load per unit fetches them (one pixel per
-// lane, 54 lanes), v_readlane moves them to scalar registers, scalar instructions pack them into (pixel, next
-// pixel) pairs of one channel, and they enter v_dot2c_f32_bf16 as its scalar operand: one instruction adds two
-// pixels' products to a sum, in fp32.  (Fetching them with scalar loads instead was four times slower: the
-// scalar data cache is no place to stream an image through.)  A wave walks units of 16 pixels of an
-// image row (W must be a multiple of 16); the four waves of a workgroup add their sums through LDS and write one
+// once.  No LDS staging and no transpose reads: both MFMA operands are gathered straight from global memory,
+// 16-bit element by element, in the layout v_mfma_f32_32x32x16_bf16 wants -- lane (r, half) fetches eight
+// consecutive pixels of row r = (tap, channel) of the shifted input (zeros outside the image; row 27 is all
+// ones, which makes the bias sum; rows 28..31 are zero) and of output channels r and 32 + r of g -- one unit (16
+// pixels of an image row; W must be a multiple of 16) ahead of the two MFMAs that use them.  (A version
+// without the matrix unit -- the input pixels moved to scalar registers and fed to v_dot2c_f32_bf16 -- took
+// 0.32 ms where this one takes 0.23; fetching those pixels with scalar loads 0.47: the scalar data cache is
+// no place to stream an image through.)  The four waves of a workgroup add their sums through LDS and write one
 // partial per workgroup, [28][64 channels]; the partials are added by wgrad_launch_reduce and spread into the
 // [9][Cout][CinP] layout (zeros in the padding columns) by a small kernel.
 // ---------------------------------------------------------------------------
@@ -303,96 +303,63 @@ struct WgradThinArgs {
     FastDiv dUnitsPerRow, dH;
 };
 
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-
-typedef unsigned short u16x2v __attribute__((ext_vector_type(2)));
-typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void conv3x3_wgrad_bf16_thin_kernel(WgradThinArgs p)
 {
-    __shared__ float red[4][kThinK][64];
+    __shared__ float red[4][32][64];
     const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int co = min((int)blockIdx.y * 64 + lane, p.Cout - 1);   // (lanes past Cout repeat the last channel; never stored)
-    float acc[kThinK];
+    const int r = lane & 31, kh8 = (lane >> 5) * 8;
+    // MFMA rows: r < 27 is (tap r / 3, channel r % 3), r == 27 a row of ones (the bias sum), the rest zero.
+    const int tap = r / 3, ci = r - tap * 3;
+    const int dy = tap / 3 - 1, dx = tap - (tap / 3) * 3 - 1;
+    const int co_a = min((int)blockIdx.y * 64 + r, p.Cout - 1), co_b = min((int)blockIdx.y * 64 + 32 + r, p.Cout - 1);
+    f32x16 acc[2];
 #pragma unroll
-    for (int k = 0; k < kThinK; ++k) acc[k] = 0.f;
-    auto dot2 = [](unsigned a, unsigned b, float c) __attribute__((always_inline)) {
-        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, a), __builtin_bit_cast(bf16x2v, b), c, false);
-    };
-    // (a, b) -> low halves of a and b / high halves of a and b in one register: one scalar pack instruction each
-    auto pack_lo = [](unsigned a, unsigned b) __attribute__((always_inline)) {
-        const u16x2v v = {(unsigned short)a, (unsigned short)b};
-        return __builtin_bit_cast(unsigned, v);
-    };
-    auto pack_hi = [](unsigned a, unsigned b) __attribute__((always_inline)) {
-        const u16x2v v = {(unsigned short)(a >> 16), (unsigned short)(b >> 16)};
-        return __builtin_bit_cast(unsigned, v);
-    };
-    // Input pixels of a unit: lane 18 kh + c (< 54) fetches the first 8 bytes (channels 0..3) of the pixel in image
-    // row h + kh - 1, column w0 + c - 1, or zeros when that lies outside the image.
-    const int xkh = lane / (kThinPx + 2), xc = lane - xkh * (kThinPx + 2);
-    // a unit's operands as loaded: this lane's channel of g for the 16 pixels, and this lane's input pixel
-    auto load_unit = [&](int u, unsigned(&gr16)[kThinPx], u32x2v &xv) __attribute__((always_inline)) {
+    for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
+    // A unit's operands as loaded (16-bit values, one per register until the unit's turn comes): the lane's
+    // eight pixels (8 kh8.. of the unit's 16) of its (tap, channel) of x, and of its two output channels of g.
+    auto load_unit = [&](int u, unsigned(&xr)[8], unsigned(&ga)[8], unsigned(&gb)[8]) __attribute__((always_inline)) {
         const int row = fast_div(u, p.dUnitsPerRow);           // = n * H + h
-        const int w0 = (u - row * p.units_per_row) * kThinPx;
+        const int w0 = (u - row * p.units_per_row) * kThinPx + kh8;
         const int n = fast_div(row, p.dH), h = row - n * p.H;
-        const unsigned short *gr = reinterpret_cast<const unsigned short *>(p.g) + ((size_t)row * p.W + w0) * p.Cout + co;
+        const unsigned short *gr = reinterpret_cast<const unsigned short *>(p.g) + ((size_t)row * p.W + w0) * p.Cout;
 #pragma unroll
-        for (int j = 0; j < kThinPx; ++j) gr16[j] = gr[(size_t)j * p.Cout];
-        const int hh = h + xkh - 1, ww = w0 + xc - 1;
-        const bool in = xkh < 3 && (unsigned)hh < (unsigned)p.H && (unsigned)ww < (unsigned)p.W;
-        // (clamped address, loaded unconditionally: a load inside a branch is waited for where the branch ends)
-        const size_t pix = in ? (size_t)(n * p.H + hh) * p.W + ww : (size_t)row * p.W + w0;
-        const u32x2v v = *reinterpret_cast<const u32x2v *>(reinterpret_cast<const char *>(p.x) + pix * p.XC * sizeof(bf16_t));
-        xv = in ? v : u32x2v{0u, 0u};
+        for (int e = 0; e < 8; ++e) {
+            ga[e] = gr[(size_t)e * p.Cout + co_a];
+            gb[e] = gr[(size_t)e * p.Cout + co_b];
+        }
+        const int hh = h + dy;
+        const bool rowok = r < 27 && (unsigned)hh < (unsigned)p.H;
+        const unsigned short *xrow = reinterpret_cast<const unsigned short *>(p.x) + ((size_t)(n * p.H + (rowok ? hh : h)) * p.W) * p.XC + ci;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int ww = w0 + e + dx;
+            const bool in = rowok && (unsigned)ww < (unsigned)p.W;
+            const unsigned v = xrow[(size_t)(in ? ww : w0) * p.XC];   // (clamped address, loaded unconditionally)
+            xr[e] = in ? v : (r == 27 ? 0x3F80u : 0u);
+        }
+    };
+    auto frag = [](const unsigned(&v)[8]) __attribute__((always_inline)) {
+        const u32x4_t w = {v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        return __builtin_bit_cast(bf16x8, w);
     };
     const int first = blockIdx.x * 4 + wv, stride = gridDim.x * 4;
-    unsigned graw[kThinPx];          // the next unit's g, one pixel per register: packed only when the unit's turn comes
-    u32x2v xnext = {0u, 0u};
+    unsigned xr[8], ga[8], gb[8];
 #pragma unroll
-    for (int j = 0; j < kThinPx; ++j) graw[j] = 0u;
-    if (first < p.units) load_unit(first, graw, xnext);
+    for (int e = 0; e < 8; ++e) { xr[e] = 0u; ga[e] = 0u; gb[e] = 0u; }
+    if (first < p.units) load_unit(first, xr, ga, gb);
     for (int u = first; u < p.units; u += stride) {
-        // two pixels of this lane's channel per register
-        unsigned gp[kThinPx / 2];
-#pragma unroll
-        for (int j = 0; j < kThinPx / 2; ++j) gp[j] = graw[2 * j] | (graw[2 * j + 1] << 16);
-        const u32x2v xv = xnext;
-        asm volatile("" : "+v"(gp[0]), "+v"(gp[1]), "+v"(gp[2]), "+v"(gp[3]), "+v"(gp[4]), "+v"(gp[5]), "+v"(gp[6]), "+v"(gp[7]));
-        if (u + stride < p.units) load_unit(u + stride, graw, xnext);   // (one unit ahead: its latency overlaps this unit's arithmetic)
-#pragma unroll
-        for (int kh = 0; kh < 3; ++kh) {
-            // the 18 pixels under this kernel row move to scalar registers (they are the same for every lane) ...
-            unsigned s01[kThinPx + 2], s2[kThinPx + 2];
-#pragma unroll
-            for (int c = 0; c < kThinPx + 2; ++c) {
-                s01[c] = __builtin_amdgcn_readlane(xv[0], kh * (kThinPx + 2) + c);
-                s2[c] = __builtin_amdgcn_readlane(xv[1], kh * (kThinPx + 2) + c);
-            }
-            // ... and are packed there into (pixel, next pixel) pairs of each channel, for the 17 adjacent column pairs
-            unsigned b0[kThinPx + 1], b1[kThinPx + 1], b2[kThinPx + 1];
-#pragma unroll
-            for (int c = 0; c <= kThinPx; ++c) {
-                b0[c] = pack_lo(s01[c], s01[c + 1]);
-                b1[c] = pack_hi(s01[c], s01[c + 1]);
-                b2[c] = pack_lo(s2[c], s2[c + 1]);
-            }
-#pragma unroll
-            for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-                for (int j = 0; j < kThinPx / 2; ++j) {
-                    const int c = 2 * j + kw;                  // output pixels 2j, 2j+1 see input columns c, c+1
-                    const int k = (kh * 3 + kw) * 3;
-                    acc[k] = dot2(gp[j], b0[c], acc[k]);
-                    acc[k + 1] = dot2(gp[j], b1[c], acc[k + 1]);
-                    acc[k + 2] = dot2(gp[j], b2[c], acc[k + 2]);
-                }
-        }
-#pragma unroll
-        for (int j = 0; j < kThinPx / 2; ++j) acc[27] = dot2(gp[j], 0x3F803F80u, acc[27]);
+        const bf16x8 xf = frag(xr), gfa = frag(ga), gfb = frag(gb);
+        if (u + stride < p.units) load_unit(u + stride, xr, ga, gb);   // (one unit ahead)
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, gfa, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, gfb, acc[1], 0, 0, 0);
     }
+    // accumulator layout: register e of lane l = row 8*(e/4) + 4*(l/32) + e%4 (tap, channel), column l%32 (output channel)
 #pragma unroll
-    for (int k = 0; k < kThinK; ++k) red[wv][k][lane] = acc[k];
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[wv][(e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)][j * 32 + r] = acc[j][e];
     __syncthreads();
     float *out = p.part + ((size_t)blockIdx.x * gridDim.y + blockIdx.y) * kThinK * 64;
     for (int e = threadIdx.x; e < kThinK * 64; e += 256) {
