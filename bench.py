@@ -291,14 +291,15 @@ def mfma_loop_ceiling():
     from paper_1810_09868_amd import binding as B
     sink = torch.empty((B.vgg_mfma_probe_sink_bytes(),), dtype=torch.uint8, device="cuda")
     out = {}
-    for name, dt, iters in (("bf16", B.BF16, 20000), ("f32", B.F32, 10000)):   # about 10 ms per launch
+    # (bf16: the 32x32x16 shape, and the 16x16x32 shape that the roofline kernel uses; about 10 ms per launch)
+    for name, dt, iters, m16 in (("bf16", B.BF16, 20000, False), ("bf16_16x16x32", B.BF16, 20000, True), ("f32", B.F32, 10000, False)):
         for rnd in (False, True):
-            B.vgg_mfma_probe(dt, rnd, iters // 2, sink)   # warm-up: the clock settles under load
+            B.vgg_mfma_probe(dt, rnd, iters // 2, sink, m16)   # warm-up: the clock settles under load
             torch.cuda.synchronize()
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
-            flops = B.vgg_mfma_probe(dt, rnd, iters, sink)
+            flops = B.vgg_mfma_probe(dt, rnd, iters, sink, m16)
             e1.record()
             torch.cuda.synchronize()
             out["%s_%s_operands_tflops" % (name, "random" if rnd else "constant")] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)

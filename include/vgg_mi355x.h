@@ -389,14 +389,18 @@ int vgg19_timed(const vgg_config *cfg, int training, const float *x_nchw, const 
 /* Measurement aid, not a step of the path: a loop of nothing but MFMA
  * instructions (register operands, 2x2 accumulator blocks, four waves per
  * SIMD on every CU), bf16 (v_mfma_f32_32x32x16_bf16) or fp32
- * (v_mfma_f32_32x32x2_f32), with all operands 1.0 (random_operands == 0) or
- * with random mantissas and signs.  Timing it gives the matrix rate this chip
+ * (v_mfma_f32_32x32x2_f32), with all operands 1.0 (bit 0 of random_operands
+ * clear) or with random mantissas and signs (set); bit 1 (bf16 only, else
+ * VGG_ERR_UNSUPPORTED) selects v_mfma_f32_16x16x32_bf16, twice as many
+ * instructions of half the size on the same operands and accumulator
+ * registers.  Timing it gives the matrix rate this chip
  * sustains at the clock it holds under that load, against which the
  * convolution kernels' rate can be read next to the data-sheet peak.
  * sink: device buffer of vgg_mfma_probe_sink_bytes() bytes (results are
  * written there so that the loop is not optimised away); *flops_host (host,
  * may be null) receives the number of floating-point operations of the launch.
- * Asynchronous on `stream`; iters > 0 else VGG_ERR_SHAPE. */
+ * Asynchronous on `stream`; iters > 0 and random_operands in 0..3 else
+ * VGG_ERR_SHAPE. */
 size_t vgg_mfma_probe_sink_bytes(void);
 int vgg_mfma_probe(int dtype, int random_operands, int iters, float *sink, size_t sink_bytes,
                    double *flops_host, void *stream);

@@ -335,9 +335,10 @@ def vgg_mfma_probe_sink_bytes() -> int:
     return lib().vgg_mfma_probe_sink_bytes()
 
 
-def vgg_mfma_probe(dtype, random_operands: bool, iters: int, sink) -> float:
+def vgg_mfma_probe(dtype, random_operands: bool, iters: int, sink, shape_16x16x32: bool = False) -> float:
     """Enqueues the MFMA-only loop; returns the number of floating-point operations it performs."""
     flops = C.c_double(0.0)
-    _chk(lib().vgg_mfma_probe(dtype, int(random_operands), iters, _ptr(sink), _nbytes(sink), C.byref(flops), _stream()),
+    mode = int(bool(random_operands)) | (2 if shape_16x16x32 else 0)
+    _chk(lib().vgg_mfma_probe(dtype, mode, iters, _ptr(sink), _nbytes(sink), C.byref(flops), _stream()),
          "vgg_mfma_probe")
     return flops.value

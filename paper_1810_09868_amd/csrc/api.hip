@@ -1010,10 +1010,11 @@ int vgg_mfma_probe(int dtype, int random_operands, int iters, float *sink, size_
 {
     if (!sink) return VGG_ERR_NULL;
     if (!dtype_ok(dtype)) return VGG_ERR_DTYPE;
-    if (iters <= 0) return VGG_ERR_SHAPE;
+    if (iters <= 0 || random_operands < 0 || random_operands > 3) return VGG_ERR_SHAPE;
+    if ((random_operands & 2) && dtype != VGG_BF16) return VGG_ERR_UNSUPPORTED;
     if (!aligned16(sink)) return VGG_ERR_ALIGN;
     if (sink_bytes < mfma_probe_sink_bytes()) return VGG_ERR_WORKSPACE;
-    return mfma_probe(dtype, random_operands != 0, iters, sink, flops_host, (hipStream_t)stream);
+    return mfma_probe(dtype, random_operands, iters, sink, flops_host, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -640,6 +640,14 @@ def test_mfma_probe_runs_and_reports_flops():
     torch.cuda.synchronize()
     vals = sink.view(torch.float32)[:256]
     assert torch.all(vals == 4 * 16 * (3 * 8 // 4) * 16.0)
+    # the 16x16x32 shape: twice the instructions, each half the size, the same sums and the same operation count
+    sink.zero_()
+    assert B.vgg_mfma_probe(B.BF16, False, 3, sink, True) == B.vgg_mfma_probe(B.BF16, False, 3, sink)
+    B.vgg_mfma_probe(B.BF16, False, 3, sink, True)
+    torch.cuda.synchronize()
+    assert torch.all(sink.view(torch.float32)[:256] == 4 * 16 * (3 * 8 // 4) * 16.0)
+    with pytest.raises(B.VggError):
+        B.vgg_mfma_probe(B.F32, False, 3, sink, True)
     small = torch.empty((16,), dtype=torch.uint8, device="cuda")
     with pytest.raises(B.VggError):
         B.vgg_mfma_probe(B.BF16, False, 3, small)
