@@ -290,6 +290,29 @@ def test_conv3x3_bf16_weights_in_registers_element_by_element(shape, kernel):
     assert max_rel_err(from_nhwc(dx), refd * (from_nhwc(xsrc) > 0)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("cout", [200, 196, 132])
+def test_conv3x3_bf16_weights_in_registers_ragged_channels(cout):
+    """The weights-in-registers kernel with a last column tile that is only partly there: 200 channels (16-byte
+    stores, the last 16-channel blocks of the tile missing), 196 (not a multiple of eight: the element-wise
+    epilogue) and 132 (four channels into the second tile); 32 input channels make the contraction a single
+    chunk.  Forward against the oracle, element by element; nothing may be written past the tensor."""
+    dtype = B.BF16
+    N, H, W, Cin = 84, 28, 28, 32
+    assert B.vgg_conv3x3_plan(B.PLAN_FWD, dtype, N, H, W, Cin, cout)[0] == 4
+    d = synth.conv_layer_inputs(N, H, W, Cin, cout, seed=cout)
+    ref = R.conv3x3_fwd(d["x"], d["w"], d["b"], relu=True)
+    x = to_nhwc(d["x"], dtype)
+    wp = _pack(dtype, d["w"])
+    n = N * H * W * cout
+    buf = torch.full((n + 4096,), -7.0, dtype=TDT[dtype], device="cuda")      # (guard behind the tensor)
+    y = buf[:n].view(N, H, W, cout)
+    ws = ws_bytes(B.vgg_conv3x3_fwd_workspace_bytes(dtype, N, H, W, Cin, cout))
+    B.vgg_conv3x3_fwd(dtype, N, H, W, Cin, cout, x, wp, dev(d["b"]), y, 1, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(from_nhwc(y), ref) <= TOL[dtype]
+    assert (buf[n:] == -7.0).all()
+
+
 def test_conv3x3_bf16_320_pixel_tiles_element_by_element():
     """The 320-pixel tiles (one workgroup per compute unit) at a size the oracle computes whole: 84 images of
     14x14 give 52 such tiles x 4 column tiles, tiles that cross image rows and images, and a ragged last tile.
